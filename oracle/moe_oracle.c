@@ -1,0 +1,441 @@
+/*
+ * CPU ORACLE -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * Plain, slow, obviously-correct implementation of one mixed-precision MoE
+ * feed-forward block: what the HIP library is checked against.  Only tests,
+ * the smoke check and the benchmark's cpu_baseline leg may call this file; it
+ * shares no code with the HIP path.
+ *
+ * What is computed follows the paper (arXiv 2407.14417):
+ *   - a gating network scores each token and gives weights to experts for a
+ *     weighted average (§1), only a top-k subset of experts is evaluated (§2.1);
+ *   - experts are parallel feed-forward layers, Mixtral 8x7B shape: 32 layers
+ *     of 8 experts, three matrices of 4096x14336 16-bit weights each (§1, §4.1);
+ *   - every expert is held either in 16-bit or in 4-bit form (§3); the gate and
+ *     the norms are always 16-bit (§3).
+ * The paper prints no formula for the block itself.  The readings used here
+ * (SwiGLU expert, softmax over the selected top-k logits, the uint4 group-64
+ * format with fp16 scale and floating zero = group minimum) are the ones fixed
+ * by the benchmark spec; they are listed in the design notes of this repository.
+ *
+ * Arithmetic: every accumulation in double; fp16 <-> fp32 conversions are
+ * written out by hand (round to nearest even).  No blocking, no fusion, no
+ * reordering: each function is the definition written as loops.  OpenMP, when
+ * enabled, splits independent output rows only.
+ *
+ * Pins (tests marked "not gpu"): half conversions against numpy over all 65536
+ * patterns and exact rational rounding; quantizer round-trip bound, exact group
+ * minimum, constant groups, nibble order on a hand-written vector; dequantizer
+ * against exact rational arithmetic; top-k against a full sort over all
+ * permutations; gates against a library softmax (k = E), k = 1, shift
+ * invariance, sum to one; expert against numpy float64 matmul and pure-Python
+ * loops; one-hot and identical-expert layer identities; RMSNorm closed form.
+ * Quality effect of quantization on a trained model (perplexity): parity
+ * unpinned, outside this build.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_GROUP 64
+
+/* ---------------------------------------------------------------- fp16 <-> fp32 */
+
+float orc_half_to_float(uint16_t h) {
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1Fu;
+    uint32_t man = h & 0x3FFu;
+    uint32_t bits;
+    if (exp == 0) {
+        if (man == 0) {
+            bits = sign;
+        } else {                                   /* subnormal: man * 2^-24 */
+            float v = (float)man * (1.0f / 16777216.0f);
+            memcpy(&bits, &v, 4);
+            bits |= sign;
+        }
+    } else if (exp == 31) {
+        bits = sign | 0x7F800000u | (man << 13);
+    } else {
+        bits = sign | ((exp + 112u) << 23) | (man << 13);
+    }
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+/* Round a double to the nearest fp16 (ties to even).  Works on the double
+ * directly, so a value that went through fp32 first and one that did not are
+ * both handled; callers that must round fp32 values pass the fp32 value. */
+uint16_t orc_double_to_half(double v) {
+    uint16_t sign = 0;
+    if (signbit(v)) { sign = 0x8000u; v = -v; }
+    if (isnan(v)) return (uint16_t)(sign | 0x7E00u);
+    if (v >= 65520.0) return (uint16_t)(sign | 0x7C00u);          /* overflow to inf */
+    if (v == 0.0) return sign;
+    int e;
+    (void)frexp(v, &e);                            /* v = m * 2^e, 0.5 <= m < 1 */
+    int ulp_exp = (e - 1 < -14) ? -24 : (e - 1 - 10); /* exponent of one unit in the last place */
+    double scaled = ldexp(v, -ulp_exp);            /* exact: power-of-two scaling */
+    double fl = floor(scaled);
+    double rem = scaled - fl;                      /* exact */
+    uint64_t q = (uint64_t)fl;
+    if (rem > 0.5 || (rem == 0.5 && (q & 1u))) q += 1;
+    /* q is now the significand in units of 2^ulp_exp: < 2048 (may be exactly 2048 after carry) */
+    if (ulp_exp == -24) {
+        return (uint16_t)(sign | (uint16_t)q);     /* subnormal or smallest normal (q == 1024) */
+    }
+    uint32_t biased = (uint32_t)(ulp_exp + 10 + 15);
+    /* q in [1024, 2048]; adding (q - 1024) with carry moves into the next exponent correctly */
+    uint32_t bits = (biased << 10) + (uint32_t)(q - 1024u);
+    return (uint16_t)(sign | bits);
+}
+
+uint16_t orc_float_to_half(float f) { return orc_double_to_half((double)f); }
+
+/* ---------------------------------------------------------------- 4-bit format */
+
+/* Nibble c of a packed row: two weights per byte, low nibble holds the even column. */
+static inline unsigned nibble_at(const uint8_t* row, int c) {
+    return (row[c >> 1] >> (4 * (c & 1))) & 0xFu;
+}
+
+/*
+ * Offline quantizer that produces 4-bit experts (the paper quantizes experts
+ * post-training with a library format, §4.1; this build's format replaces it).
+ * Per group of 64 consecutive columns of one row:
+ *   zero  = group minimum (an fp16 value, kept exactly)
+ *   scale = fp16_rne( (fp32(max) - fp32(min)) / 15 )         fp32 arithmetic
+ *   q     = clamp( rint( (fp32(w) - fp32(zero)) / fp32(scale) ), 0, 15 ), all 0 if scale == 0
+ * w: fp16 [out,in]; q_packed: [out,in/2]; scale, zero: fp16 [out,in/64].
+ * Returns 0, or -1 if `in` is not a multiple of 64.
+ */
+int orc_quantize_int4(const uint16_t* w, int out, int in, uint8_t* q_packed,
+                      uint16_t* scale, uint16_t* zero) {
+    if (in % ORC_GROUP != 0 || out < 0) return -1;
+    const int groups = in / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < out; ++r) {
+        const uint16_t* wr = w + (size_t)r * in;
+        uint8_t* qr = q_packed + (size_t)r * (in / 2);
+        for (int g = 0; g < groups; ++g) {
+            float mn = orc_half_to_float(wr[g * ORC_GROUP]);
+            float mx = mn;
+            uint16_t mn_bits = wr[g * ORC_GROUP];
+            for (int j = 1; j < ORC_GROUP; ++j) {
+                float v = orc_half_to_float(wr[g * ORC_GROUP + j]);
+                if (v < mn) { mn = v; mn_bits = wr[g * ORC_GROUP + j]; }
+                if (v > mx) mx = v;
+            }
+            volatile float range = mx - mn;        /* volatile: keep each step a rounded fp32 */
+            volatile float step = range / 15.0f;
+            uint16_t s_bits = orc_float_to_half(step);
+            float s = orc_half_to_float(s_bits);
+            scale[(size_t)r * groups + g] = s_bits;
+            zero[(size_t)r * groups + g] = mn_bits;
+            for (int j = 0; j < ORC_GROUP; ++j) {
+                int c = g * ORC_GROUP + j;
+                unsigned q = 0;
+                if (s != 0.0f) {
+                    volatile float diff = orc_half_to_float(wr[c]) - mn;
+                    volatile float ratio = diff / s;
+                    float rq = rintf(ratio);       /* default rounding mode: nearest even */
+                    if (rq < 0.0f) rq = 0.0f;
+                    if (rq > 15.0f) rq = 15.0f;
+                    q = (unsigned)rq;
+                }
+                if (c & 1) qr[c >> 1] = (uint8_t)((qr[c >> 1] & 0x0Fu) | (q << 4));
+                else       qr[c >> 1] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Dequantizer: w_hat[r,c] = fp16_rne( fp32(q[r,c]) * fp32(scale[r,c/64]) + fp32(zero[r,c/64]) ).
+ * The product is exact in fp32 (4-bit times 11-bit significand); the sum is
+ * rounded to fp32, then to fp16.
+ */
+static void dequant_row(const uint8_t* qrow, const uint16_t* srow, const uint16_t* zrow,
+                        int in, uint16_t* out_row) {
+    for (int c = 0; c < in; ++c) {
+        float s = orc_half_to_float(srow[c / ORC_GROUP]);
+        float z = orc_half_to_float(zrow[c / ORC_GROUP]);
+        volatile float prod = (float)nibble_at(qrow, c) * s;
+        volatile float sum = prod + z;
+        out_row[c] = orc_float_to_half(sum);
+    }
+}
+
+int orc_dequant_int4(const uint8_t* q_packed, const uint16_t* scale, const uint16_t* zero,
+                     int out, int in, uint16_t* w_hat) {
+    if (in % ORC_GROUP != 0 || out < 0) return -1;
+    const int groups = in / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < out; ++r)
+        dequant_row(q_packed + (size_t)r * (in / 2), scale + (size_t)r * groups,
+                    zero + (size_t)r * groups, in, w_hat + (size_t)r * in);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- gating (§1, §2.1) */
+
+/*
+ * Router logits, top-k and gates for T tokens.
+ *   logit[t,e] = sum_j x[t,j] * Wg[e,j]  (+ bias[e])                double
+ *   idx[t,:]   = the k experts with the largest logits, descending; equal logits -> lower index first
+ *   gate[t,s]  = exp(l_s - l_0) / sum_{s'<k} exp(l_s' - l_0)        softmax over the selected logits
+ * x: fp16 [T,d]; wg: fp16 [E,d]; bias: fp32 [E] or NULL; idx: int32 [T,k]; gate: fp32 [T,k];
+ * logits_out: double [T,E] or NULL.
+ */
+int orc_route(const uint16_t* x, int T, int d, const uint16_t* wg, const float* bias, int E, int k,
+              int32_t* idx, float* gate, double* logits_out) {
+    if (T < 0 || d < 1 || E < 1 || k < 1 || k > E) return -1;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        double* l = (double*)malloc(sizeof(double) * (size_t)E);
+        char* taken = (char*)calloc((size_t)E, 1);
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int j = 0; j < d; ++j)
+                acc += (double)orc_half_to_float(x[(size_t)t * d + j]) *
+                       (double)orc_half_to_float(wg[(size_t)e * d + j]);
+            if (bias) acc += (double)bias[e];
+            l[e] = acc;
+            if (logits_out) logits_out[(size_t)t * E + e] = acc;
+        }
+        for (int s = 0; s < k; ++s) {              /* k selection passes */
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || l[e] > l[best]) best = e;   /* strict >: ties keep the lower index */
+            }
+            taken[best] = 1;
+            idx[(size_t)t * k + s] = best;
+        }
+        double m = l[idx[(size_t)t * k]];
+        double denom = 0.0;
+        for (int s = 0; s < k; ++s) denom += exp(l[idx[(size_t)t * k + s]] - m);
+        for (int s = 0; s < k; ++s)
+            gate[(size_t)t * k + s] = (float)(exp(l[idx[(size_t)t * k + s]] - m) / denom);
+        free(l);
+        free(taken);
+    }
+    return 0;
+}
+
+/*
+ * Grouping of (token, slot) pairs by expert.  Flat pair index p = t*k + s.
+ *   counts[e]   = number of pairs routed to e
+ *   offsets[e]  = exclusive prefix sum of counts, offsets[E] = T*k
+ *   perm[r]     = flat pair index held by grouped row r; rows of one expert are contiguous
+ *                 (offsets[e] .. offsets[e+1]-1) and keep increasing flat index.
+ */
+int orc_permute(const int32_t* idx, int T, int k, int E, int32_t* counts, int32_t* offsets, int32_t* perm) {
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    for (int p = 0; p < T * k; ++p) {
+        if (idx[p] < 0 || idx[p] >= E) return -1;
+        counts[idx[p]] += 1;
+    }
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    int32_t* cursor = (int32_t*)malloc(sizeof(int32_t) * (size_t)E);
+    for (int e = 0; e < E; ++e) cursor[e] = offsets[e];
+    for (int p = 0; p < T * k; ++p) perm[cursor[idx[p]]++] = p;
+    free(cursor);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- expert FFN (§1: experts are feed-forward layers) */
+
+/* One weight matrix [out,in]: 16-bit (data = fp16 [out,in], scale = zero = NULL)
+ * or 4-bit (data = packed [out,in/2], scale/zero fp16 [out,in/64]). */
+typedef struct {
+    const void* data;
+    const uint16_t* scale;
+    const uint16_t* zero;
+} orc_mat;
+
+/* Row r of a matrix as doubles; 4-bit rows go through the dequantizer first, so
+ * a 4-bit expert is by construction the 16-bit expert made of its dequantized weights. */
+static void mat_row(const orc_mat* m, int prec_int4, int r, int in, double* row, uint16_t* tmp) {
+    const uint16_t* src;
+    if (prec_int4) {
+        const int groups = in / ORC_GROUP;
+        dequant_row((const uint8_t*)m->data + (size_t)r * (in / 2), m->scale + (size_t)r * groups,
+                    m->zero + (size_t)r * groups, in, tmp);
+        src = tmp;
+    } else {
+        src = (const uint16_t*)m->data + (size_t)r * in;
+    }
+    for (int c = 0; c < in; ++c) row[c] = (double)orc_half_to_float(src[c]);
+}
+
+/*
+ * SwiGLU expert on n rows:  a = W1 x, b = W3 x, h = a / (1 + exp(-a)) * b, y = W2 h.
+ * x_rows: fp16 [n,d]; y: double [n,d_model]; h is kept in double, never rounded.
+ * h_out: optional double [n,f].
+ */
+int orc_expert_ffn(int prec_int4, const orc_mat* w1, const orc_mat* w3, const orc_mat* w2,
+                   const uint16_t* x_rows, int n, int d, int f, double* y, double* h_out) {
+    if (n < 0 || d < 1 || f < 1) return -1;
+    if (prec_int4 && (d % ORC_GROUP != 0 || f % ORC_GROUP != 0)) return -1;
+    if (n == 0) return 0;
+    double* xd = (double*)malloc(sizeof(double) * (size_t)n * d);
+    double* h = (double*)malloc(sizeof(double) * (size_t)n * f);
+    for (size_t i = 0; i < (size_t)n * d; ++i) xd[i] = (double)orc_half_to_float(x_rows[i]);
+#pragma omp parallel
+    {
+        double* row1 = (double*)malloc(sizeof(double) * (size_t)d);
+        double* row3 = (double*)malloc(sizeof(double) * (size_t)d);
+        uint16_t* tmp = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)(d > f ? d : f));
+#pragma omp for schedule(static)
+        for (int r = 0; r < f; ++r) {
+            mat_row(w1, prec_int4, r, d, row1, tmp);
+            mat_row(w3, prec_int4, r, d, row3, tmp);
+            for (int i = 0; i < n; ++i) {
+                double a = 0.0, b = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    a += row1[j] * xd[(size_t)i * d + j];
+                    b += row3[j] * xd[(size_t)i * d + j];
+                }
+                h[(size_t)i * f + r] = a / (1.0 + exp(-a)) * b;
+            }
+        }
+        free(row1);
+        free(row3);
+        double* row2 = (double*)malloc(sizeof(double) * (size_t)f);
+#pragma omp for schedule(static)
+        for (int r = 0; r < d; ++r) {
+            mat_row(w2, prec_int4, r, f, row2, tmp);
+            for (int i = 0; i < n; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < f; ++j) acc += row2[j] * h[(size_t)i * f + j];
+                y[(size_t)i * d + r] = acc;
+            }
+        }
+        free(row2);
+        free(tmp);
+    }
+    if (h_out) memcpy(h_out, h, sizeof(double) * (size_t)n * f);
+    free(xd);
+    free(h);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- whole block */
+
+typedef struct {
+    int prec_int4;      /* the "quantized?" attribute of the paper's expert table (§3) */
+    int resident;       /* the location attribute (§3): 1 = in device memory */
+    orc_mat w1, w3, w2;
+} orc_expert;
+
+/*
+ * One MoE block on T tokens:  out[t,:] = sum_{s<k} gate[t,s] * FFN_{idx[t,s]}(x[t,:]).
+ * out: double [T,d] (unrounded); idx_out / gate_out optional.
+ * Returns 0, -1 on bad shapes, -3 if a routed expert is not resident.
+ */
+int orc_layer_forward(const uint16_t* x, int T, int d, int f, int E, int k, const uint16_t* wg,
+                      const float* bias, const orc_expert* experts, double* out, int32_t* idx_out,
+                      float* gate_out) {
+    if (T < 1 || k > E) return -1;
+    int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)T * k);
+    float* gate = (float*)malloc(sizeof(float) * (size_t)T * k);
+    int rc = orc_route(x, T, d, wg, bias, E, k, idx, gate, NULL);
+    if (rc == 0) {
+        for (int p = 0; p < T * k; ++p)
+            if (!experts[idx[p]].resident || !experts[idx[p]].w1.data) rc = -3;
+    }
+    if (rc != 0) { free(idx); free(gate); return rc; }
+    /* y of every (token, slot) pair, then the weighted sum in slot order */
+    double* ypair = (double*)malloc(sizeof(double) * (size_t)T * k * d);
+    uint16_t* xrow = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * d);
+    double* ye = (double*)malloc(sizeof(double) * (size_t)T * d);
+    int32_t* who = (int32_t*)malloc(sizeof(int32_t) * (size_t)T);
+    for (int e = 0; e < E; ++e) {
+        int n = 0;
+        for (int p = 0; p < T * k; ++p) {
+            if (idx[p] != e) continue;
+            memcpy(xrow + (size_t)n * d, x + (size_t)(p / k) * d, sizeof(uint16_t) * (size_t)d);
+            who[n++] = p;
+        }
+        if (n == 0) continue;
+        orc_expert_ffn(experts[e].prec_int4, &experts[e].w1, &experts[e].w3, &experts[e].w2, xrow, n, d, f, ye, NULL);
+        for (int i = 0; i < n; ++i)
+            memcpy(ypair + (size_t)who[i] * d, ye + (size_t)i * d, sizeof(double) * (size_t)d);
+    }
+    for (int t = 0; t < T; ++t)
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int s = 0; s < k; ++s)
+                acc += (double)gate[(size_t)t * k + s] * ypair[((size_t)t * k + s) * d + c];
+            out[(size_t)t * d + c] = acc;
+        }
+    if (idx_out) memcpy(idx_out, idx, sizeof(int32_t) * (size_t)T * k);
+    if (gate_out) memcpy(gate_out, gate, sizeof(float) * (size_t)T * k);
+    free(ypair); free(xrow); free(ye); free(who); free(idx); free(gate);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- chain glue (non-expert layers stay 16-bit, §3) */
+
+/* n[t,:] = fp16_rne( h[t,:] / sqrt(mean(h[t,:]^2) + eps) * g ) */
+void orc_rmsnorm(const uint16_t* h, const uint16_t* g, int T, int d, double eps, uint16_t* n) {
+    for (int t = 0; t < T; ++t) {
+        double ss = 0.0;
+        for (int j = 0; j < d; ++j) {
+            double v = (double)orc_half_to_float(h[(size_t)t * d + j]);
+            ss += v * v;
+        }
+        double inv = 1.0 / sqrt(ss / (double)d + eps);
+        for (int j = 0; j < d; ++j)
+            n[(size_t)t * d + j] = orc_double_to_half((double)orc_half_to_float(h[(size_t)t * d + j]) * inv *
+                                                      (double)orc_half_to_float(g[j]));
+    }
+}
+
+/* h[t,:] <- fp16_rne( h[t,:] + moe_out[t,:] ), moe_out unrounded double */
+void orc_residual_add(uint16_t* h, const double* moe_out, int T, int d) {
+    for (size_t i = 0; i < (size_t)T * d; ++i)
+        h[i] = orc_double_to_half((double)orc_half_to_float(h[i]) + moe_out[i]);
+}
+
+/* One block of the chained configuration: RMSNorm -> MoE -> residual add, in place on h. */
+int orc_chain_layer(uint16_t* h, int T, int d, int f, int E, int k, const uint16_t* rms_gain, double eps,
+                    const uint16_t* wg, const float* bias, const orc_expert* experts, int32_t* idx_out,
+                    float* gate_out, uint16_t* normed_out) {
+    uint16_t* n = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * d);
+    double* out = (double*)malloc(sizeof(double) * (size_t)T * d);
+    orc_rmsnorm(h, rms_gain, T, d, eps, n);
+    int rc = orc_layer_forward(n, T, d, f, E, k, wg, bias, experts, out, idx_out, gate_out);
+    if (rc == 0) orc_residual_add(h, out, T, d);
+    if (normed_out) memcpy(normed_out, n, sizeof(uint16_t) * (size_t)T * d);
+    free(n);
+    free(out);
+    return rc;
+}
+
+/* ---------------------------------------------------------------- threads */
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

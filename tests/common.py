@@ -1,0 +1,178 @@
+"""Shared test helpers: workload builders on top of the seeded generator, exact
+rational fp16 rounding for pins, and the parity metrics.  Nothing here calls the
+HIP path; builders that need quantized experts use the oracle's quantizer."""
+from __future__ import annotations
+
+import bisect
+from dataclasses import dataclass, field
+from fractions import Fraction
+from typing import List, Optional
+
+import numpy as np
+
+from paper_2407_14417_amd import synth
+
+# ---------------------------------------------------------------- exact fp16 rounding (independent of the oracle)
+
+_ALL_BITS = np.arange(0x7C00, dtype=np.uint16)                  # non-negative finite halves, ascending
+_ALL_VALS = [Fraction(float(v)) for v in _ALL_BITS.view(np.float16).astype(np.float64)]
+
+
+def half_rne_exact(v: Fraction) -> int:
+    """Bits of the fp16 nearest to the exact rational ``v`` (ties to even significand), by search over
+    every finite fp16 value."""
+    sign = 0x8000 if v < 0 else 0
+    a = -v if v < 0 else v
+    top = _ALL_VALS[-1]
+    if a >= top + (top - _ALL_VALS[-2]) / 2:                    # 65520 and above round to infinity
+        return sign | 0x7C00
+    i = bisect.bisect_left(_ALL_VALS, a)
+    if i < len(_ALL_VALS) and _ALL_VALS[i] == a:
+        return sign | i
+    if i >= len(_ALL_VALS):
+        return sign | (len(_ALL_VALS) - 1)
+    lo, hi = i - 1, i
+    dlo, dhi = a - _ALL_VALS[lo], _ALL_VALS[hi] - a
+    if dlo < dhi:
+        return sign | lo
+    if dhi < dlo:
+        return sign | hi
+    return sign | (lo if lo % 2 == 0 else hi)
+
+
+def float_rne_exact(v: Fraction) -> Fraction:
+    """Exact rational -> nearest fp32 (ties to even), returned as a Fraction.  Uses integer arithmetic only."""
+    if v == 0:
+        return Fraction(0)
+    s = -1 if v < 0 else 1
+    a = -v if v < 0 else v
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    e = max(e, -126)
+    ulp = Fraction(2) ** (e - 23)
+    q = a / ulp
+    fl = q.numerator // q.denominator
+    rem = q - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return s * fl * ulp
+
+
+# ---------------------------------------------------------------- parity metrics (tolerances of the benchmark spec)
+
+MAX_ERR_FRAC = 1e-2      # max |err| <= 1e-2 * max |ref|
+REL_L2 = 2e-3            # ||err||_2 / ||ref||_2 <= 2e-3
+
+
+def ffn_errors(got: np.ndarray, ref: np.ndarray):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    err = got - ref
+    max_frac = float(np.abs(err).max() / max(np.abs(ref).max(), 1e-300))
+    rel_l2 = float(np.linalg.norm(err) / max(np.linalg.norm(ref), 1e-300))
+    return max_frac, rel_l2
+
+
+def assert_ffn_close(got, ref, what=""):
+    max_frac, rel_l2 = ffn_errors(got, ref)
+    assert max_frac <= MAX_ERR_FRAC and rel_l2 <= REL_L2, f"{what}: max|err|/max|ref|={max_frac:.3e} relL2={rel_l2:.3e}"
+    return max_frac, rel_l2
+
+
+# ---------------------------------------------------------------- workloads
+
+@dataclass
+class Config:
+    name: str
+    d: int
+    f: int
+    E: int
+    k: int
+    T: int
+    int4_experts: tuple
+    seed: int = 0
+    router: str = "normal"          # "normal": Wg ~ N(0, 0.02); "uniform": Wg ~ U(+-0.02*sqrt(3))
+    zipf: Optional[float] = None    # exponent of the per-expert logit offsets, None = no bias
+    layer: int = 0
+
+
+TINY = Config("tiny", 256, 512, 4, 2, 16, (1, 3))
+DECODE = Config("decode_b1", 4096, 14336, 8, 2, 1, (4, 5, 6, 7))
+BATCHED = Config("batched_int4", 4096, 14336, 8, 2, 16, tuple(range(8)), router="uniform")
+PREFILL = Config("prefill", 4096, 14336, 8, 2, 512, (2, 3, 4, 5, 6, 7), zipf=1.2)
+# Same structure as the Mixtral-shaped configurations at a size the oracle finishes in seconds;
+# d and f are not multiples of the kernels' larger tiles, T*k/E is ragged.
+MEDIUM = Config("medium", 1024, 2816, 8, 2, 24, (1, 2, 5, 7))
+MEDIUM_ZIPF = Config("medium_zipf", 1024, 2816, 8, 2, 96, (2, 3, 4, 5, 6, 7), zipf=1.2)
+
+
+def gate_matrix(cfg: Config) -> np.ndarray:
+    if cfg.router == "uniform":
+        return synth.uniform_f16((cfg.E, cfg.d), 0.02 * 3 ** 0.5, cfg.seed, synth.STREAM_WG + 16 * cfg.layer)
+    return synth.normal_f16((cfg.E, cfg.d), 0.02, cfg.seed, synth.STREAM_WG + 16 * cfg.layer)
+
+
+def gate_bias(cfg: Config) -> Optional[np.ndarray]:
+    return None if cfg.zipf is None else synth.zipf_bias(cfg.E, cfg.zipf)
+
+
+def expert_weights_f16(cfg: Config, e: int):
+    """(w1 [f,d], w3 [f,d], w2 [d,f]) ~ N(0, 0.02), fp16."""
+    w1 = synth.normal_f16((cfg.f, cfg.d), 0.02, cfg.seed, synth.expert_stream(cfg.layer, e, 0))
+    w3 = synth.normal_f16((cfg.f, cfg.d), 0.02, cfg.seed, synth.expert_stream(cfg.layer, e, 1))
+    w2 = synth.normal_f16((cfg.d, cfg.f), 0.02, cfg.seed, synth.expert_stream(cfg.layer, e, 2))
+    return w1, w3, w2
+
+
+def logits_f64(x: np.ndarray, wg: np.ndarray, bias: Optional[np.ndarray]) -> np.ndarray:
+    """Router logits by a library float64 matmul: used only to keep generated tokens away from top-k ties."""
+    l = x.astype(np.float64) @ wg.astype(np.float64).T
+    if bias is not None:
+        l = l + bias.astype(np.float64)
+    return l
+
+
+def tokens_with_margin(cfg: Config, wg: np.ndarray, bias: Optional[np.ndarray], margin: float = 1e-3,
+                       T: Optional[int] = None) -> np.ndarray:
+    """x ~ N(0,1) fp16 [T,d].  A token whose top-(k+1) sorted logits have an adjacent gap below ``margin`` is
+    redrawn from the retry stream, so that top-k indices and their order are decided with a margin that fp32
+    and fp64 accumulation both respect."""
+    T = cfg.T if T is None else T
+    x = synth.normal_f16((T, cfg.d), 1.0, cfg.seed, synth.x_stream(0))
+    for retry in range(1, 64):
+        l = np.sort(logits_f64(x, wg, bias), axis=1)[:, ::-1]
+        top = l[:, : min(cfg.k + 1, cfg.E)]
+        bad = np.where((top[:, :-1] - top[:, 1:]).min(axis=1) < margin)[0]
+        if bad.size == 0:
+            return x
+        for t in bad:
+            x[t] = synth.normal_f16((cfg.d,), 1.0, cfg.seed, synth.x_stream(retry), first=int(t) * cfg.d)
+    raise RuntimeError("could not separate top-k logits")
+
+
+@dataclass
+class Workload:
+    cfg: Config
+    x: np.ndarray
+    wg: np.ndarray
+    bias: Optional[np.ndarray]
+    experts: list                    # oracle Expert objects (numpy-backed)
+
+
+def build_workload(cfg: Config, orc, experts_needed=None) -> Workload:
+    """Host-side tensors of one configuration.  ``experts_needed``: build only these experts (others None)."""
+    wg = gate_matrix(cfg)
+    bias = gate_bias(cfg)
+    x = tokens_with_margin(cfg, wg, bias)
+    experts = []
+    for e in range(cfg.E):
+        if experts_needed is not None and e not in experts_needed:
+            experts.append(None)
+            continue
+        w1, w3, w2 = expert_weights_f16(cfg, e)
+        if e in cfg.int4_experts:
+            experts.append(orc.Expert(orc.quantize_int4(w1), orc.quantize_int4(w3), orc.quantize_int4(w2)))
+        else:
+            experts.append(orc.Expert(orc.Mat(w1), orc.Mat(w3), orc.Mat(w2)))
+    return Workload(cfg, x, wg, bias, experts)
