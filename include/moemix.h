@@ -1,0 +1,197 @@
+/*
+ * moemix -- one Mixture-of-Experts feed-forward block in which every expert is
+ * held either in 16-bit or in 4-bit form, for AMD MI355X (gfx950).
+ *
+ * Method: "Mixture of Experts with Mixture of Precisions for Tuning Quality of
+ * Service" (arXiv 2407.14417).  The paper serves an MoE model whose experts are
+ * partially quantized (§3): an expert table carries two attributes per expert,
+ * "quantized?" and "on the GPU?"; the number of 4-bit experts is the knob that
+ * trades quality for memory/throughput.  This library is the compute under that
+ * policy: the gating network with top-k selection (§1, §2.1), the experts as
+ * parallel feed-forward layers of Mixtral shape (§1, §4.1), each evaluated in
+ * the precision its table entry names, and the weighted average of the selected
+ * experts' outputs (§1).  The policy itself (how many experts to quantize,
+ * which to keep resident) stays with the caller and reaches the library as the
+ * per-expert `prec` and `resident` fields.
+ *
+ * Conventions
+ *   - Every pointer argument documented "device" is GPU memory owned by the
+ *     caller; "host" is ordinary host memory.  The library never frees or keeps
+ *     a caller's pointer beyond the call, and allocates nothing.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as
+ *     void*) and returns; nothing synchronizes except moe_read_status.
+ *     All launches are capturable into a HIP graph.
+ *   - Return value: MOE_OK or a negative moe_status.  No call throws or exits.
+ *     moe_last_error() gives a host string for the last failure on this thread.
+ *   - Matrices are row-major [out, in]; `in` is the contraction dimension.
+ *   - 16-bit means IEEE fp16.  4-bit means: asymmetric uint4, groups of 64
+ *     consecutive columns of one row share an fp16 scale and an fp16 zero,
+ *     two codes per byte, the even column in the low nibble;
+ *     dequantized weight = fp16_rne( fp32(code) * fp32(scale) + fp32(zero) ).
+ *   - d_model and d_ff must be multiples of 64; n_experts <= MOE_MAX_EXPERTS;
+ *     1 <= top_k <= min(n_experts, MOE_MAX_TOPK).
+ */
+#ifndef MOEMIX_H
+#define MOEMIX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_GROUP 64
+#define MOE_MAX_EXPERTS 32
+#define MOE_MAX_TOPK 8
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_EINVAL = -1,       /* null pointer, negative size */
+    MOE_ESHAPE = -2,       /* shape outside what the kernels support (see above) */
+    MOE_ENOTRESIDENT = -3, /* an expert that had to run is not in device memory */
+    MOE_EWORKSPACE = -4,   /* workspace missing or smaller than moe_workspace_bytes */
+    MOE_EHIP = -5          /* a HIP runtime call failed */
+} moe_status;
+
+/* The "quantized?" attribute of the paper's expert table (§3). */
+typedef enum { MOE_PREC_FP16 = 0, MOE_PREC_INT4G64 = 1 } moe_prec;
+
+/* One weight matrix [out, in] in device memory. */
+typedef struct {
+    const void* data;  /* device: fp16 [out,in], or uint8 [out,in/2] of packed codes */
+    const void* scale; /* device: fp16 [out,in/64]; NULL for a 16-bit matrix */
+    const void* zero;  /* device: fp16 [out,in/64]; NULL for a 16-bit matrix */
+} moe_mat;
+
+/* One expert = SwiGLU feed-forward layer y = W2 ( silu(W1 x) * (W3 x) ).
+ * w1, w3: [d_ff, d_model]; w2: [d_model, d_ff]; all three in precision `prec`. */
+typedef struct {
+    int32_t prec;     /* moe_prec */
+    int32_t resident; /* location attribute of the expert table (§3): 1 = matrices are in device memory */
+    moe_mat w1, w3, w2;
+} moe_expert;
+
+/* One MoE block.  `experts` is a HOST array of n_experts descriptors holding device pointers. */
+typedef struct {
+    int32_t d_model, d_ff, n_experts, top_k;
+    const void* w_gate;        /* device: fp16 [n_experts, d_model], always 16-bit (§3: non-expert parts stay 16-bit) */
+    const float* gate_bias;    /* device: fp32 [n_experts] added to the router logits, or NULL */
+    const moe_expert* experts; /* host */
+} moe_layer;
+
+typedef void* moe_stream_t; /* hipStream_t; NULL = the default stream */
+
+/* Bytes of scratch that the calls below need for `n_tokens` tokens of `layer`.  Host-only arithmetic.
+ * The caller allocates that many bytes of device memory (256-byte aligned) and passes them as `ws`;
+ * one workspace must not be used by two calls that may overlap in time.  Returns 0 on bad arguments. */
+size_t moe_workspace_bytes(const moe_layer* layer, int n_tokens);
+
+/*
+ * Gating network (§1) with top-k selection (§2.1), one fused kernel.
+ *   logit[t,e] = sum_j x[t,j] * w_gate[e,j] (+ gate_bias[e])       fp32 accumulation
+ *   topk_idx[t,:]  = the top_k experts by logit, descending; equal logits: lower index first
+ *   topk_gate[t,:] = softmax over those top_k logits (weights of the weighted average, sum to 1)
+ * x: device fp16 [T, d_model]; topk_idx: device int32 [T, top_k]; topk_gate: device fp32 [T, top_k].
+ */
+int moe_route(const moe_layer* layer, const void* x, int T, int32_t* topk_idx, float* topk_gate,
+              moe_stream_t stream);
+
+/*
+ * Grouping of the T*top_k (token, slot) pairs by expert (the scatter of tokens to experts that
+ * top-k gating implies, §2.1).  Flat pair index p = t*top_k + s.
+ *   counts[e]  = pairs routed to expert e;  offsets = exclusive prefix sum, offsets[E] = T*top_k
+ *   perm[r]    = flat pair index held by grouped row r; one expert's rows are contiguous and keep
+ *                increasing pair index (the result is unique).
+ * topk_idx: device int32 [T, top_k]; counts: device int32 [E]; offsets: device int32 [E+1];
+ * perm: device int32 [T*top_k].  An index outside [0, E) sets the MOE_EINVAL bit readable with
+ * moe_read_status on `ws` and its pair is dropped.
+ */
+int moe_permute(const moe_layer* layer, const int32_t* topk_idx, int T, int32_t* counts, int32_t* offsets,
+                int32_t* perm, void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * One expert's feed-forward layer on n rows (§1: experts are parallel FF layers), in the precision
+ * its descriptor names (§3), 4-bit weights being dequantized inside the matrix kernels:
+ *   y[i,:] = W2 ( silu(W1 x_i) * (W3 x_i) )                        fp32 accumulation
+ * x_rows: device fp16 [n, d_model]; y: device fp32 [n, d_model] (overwritten).
+ * Fails with MOE_ENOTRESIDENT on the host if the expert is not resident.
+ */
+int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows, int n, float* y, void* ws,
+                         size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * The whole block on T tokens: gating, top-k, grouping, every selected expert in its own precision,
+ * weighted average (§1, §2.1, §3):
+ *   out[t,:] = fp16_rne( sum_s topk_gate[t,s] * FFN_{topk_idx[t,s]}(x[t,:]) )
+ * x: device fp16 [T, d_model]; out: device fp16 [T, d_model];
+ * topk_idx_out / topk_gate_out: device [T, top_k], nullable.
+ * Routing happens on the device, so a routed expert that is not resident cannot fail the call on the
+ * host: its contribution is left out and the MOE_ENOTRESIDENT bit is set in the workspace status
+ * (moe_read_status).  No host synchronization inside.
+ */
+int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, int32_t* topk_idx_out,
+                      float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * Chain of n_layers blocks as in a decoder stack whose non-expert parts are reduced to the 16-bit
+ * glue (§3: non-expert layers are always 16-bit):  for each layer
+ *   n = fp16_rne( h / sqrt(mean(h^2) + eps) * rms_gain[layer] );   h <- fp16_rne( h + MoE_layer(n) )
+ * layers: host array [n_layers]; rms_gain: host array of n_layers device pointers to fp16 [d_model];
+ * h: device fp16 [T, d_model], updated in place; topk_idx_out: device int32 [n_layers, T, top_k] or NULL.
+ * All layers must share d_model, d_ff, n_experts, top_k.  ws sized by moe_workspace_bytes(&layers[0], T).
+ */
+int moe_chain_forward(const moe_layer* layers, const void* const* rms_gain, int n_layers, float eps, void* h,
+                      int T, int32_t* topk_idx_out, void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * Dequantize one 4-bit matrix to fp16 (check hook for the format; also what a switch of an expert
+ * from 4-bit to 16-bit form needs, §3 "partial reconfiguration"):
+ *   w_fp16[r,c] = fp16_rne( fp32(code[r,c]) * fp32(scale[r,c/64]) + fp32(zero[r,c/64]) )
+ * m: 4-bit matrix [out,in]; w_fp16: device fp16 [out,in].
+ */
+int moe_dequant_int4(const moe_mat* m, int out, int in, void* w_fp16, moe_stream_t stream);
+
+/*
+ * Quantize one fp16 matrix to the 4-bit form on the device (switching an expert from 16-bit to
+ * 4-bit without a host round trip, §3 "switching between quantized and 16-bit formats").
+ * Per group of 64 columns: zero = min; scale = fp16_rne((fp32(max) - fp32(min)) / 15);
+ * code = clamp(rint((fp32(w) - fp32(zero)) / fp32(scale)), 0, 15), all codes 0 when scale == 0.
+ * w_fp16: device fp16 [out,in]; packed: device uint8 [out,in/2]; scale, zero: device fp16 [out,in/64].
+ */
+int moe_quantize_int4(const void* w_fp16, int out, int in, void* packed, void* scale, void* zero,
+                      moe_stream_t stream);
+
+/*
+ * Seeded synthetic tensors written directly in device memory (stand-ins for trained weights and real
+ * activations): element i of the stream is a pure function of (seed, stream_id, first + i).
+ * kind 0: sum-of-eight-uniforms "normal" stream, kind 1: uniform stream; `scale` is the fp32 factor
+ * applied to the integer draw before rounding to fp16.  dst: device fp16 [n].
+ */
+int moe_synth_fill_f16(void* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale,
+                       int kind, moe_stream_t stream);
+
+/* Waits for `stream`, then reads the status word of `ws`: OR of (1 << -code) over the device-side conditions
+ * raised by the most recent moe_layer_forward / moe_chain_forward / moe_permute call that used `ws`
+ * (bit 3: a routed expert was not resident; bit 1: an expert index outside [0, n_experts)). */
+int moe_read_status(void* ws, moe_stream_t stream, int* status_bits);
+
+/*
+ * Measurement hook: the next launch of kernel `kernel` made by this thread is bracketed by
+ * hipEventRecord(start_event) / hipEventRecord(stop_event) on the stream it is launched on (one shot;
+ * arm again for the next launch).  Events are hipEvent_t created by the caller with timing enabled.
+ */
+enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_PERMUTE = 1, MOE_KERNEL_UP = 2, MOE_KERNEL_DOWN = 3, MOE_KERNEL_COMBINE = 4,
+       MOE_KERNEL_RMSNORM = 5 };
+int moe_trace_kernel(int kernel, void* start_event, void* stop_event);
+
+/* Host string describing the last error returned on this thread ("" if none). */
+const char* moe_last_error(void);
+
+/* Library version, 1000*major + minor. */
+int moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEMIX_H */

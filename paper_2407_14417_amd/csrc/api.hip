@@ -1,0 +1,254 @@
+// C-ABI entry points of libmoemix (declared and documented in include/moemix.h): argument
+// checks, workspace carving, kernel sequencing.  No allocation, no synchronization except in
+// moe_read_status.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace moemix;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_hip(hipStream_t) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+    return MOE_OK;
+}
+
+int check_layer(const moe_layer* L) {
+    if (!L) return fail(MOE_EINVAL, "layer is NULL");
+    if (!L->w_gate || !L->experts) return fail(MOE_EINVAL, "layer.w_gate / layer.experts is NULL");
+    if (L->d_model < 64 || L->d_ff < 64 || L->d_model % MOE_GROUP || L->d_ff % MOE_GROUP)
+        return fail(MOE_ESHAPE, "d_model=%d and d_ff=%d must be positive multiples of %d", L->d_model, L->d_ff, MOE_GROUP);
+    if (L->d_model > 8192 || L->d_ff > 16384)
+        return fail(MOE_ESHAPE, "d_model=%d > 8192 or d_ff=%d > 16384 not supported", L->d_model, L->d_ff);
+    if (L->n_experts < 1 || L->n_experts > MOE_MAX_EXPERTS)
+        return fail(MOE_ESHAPE, "n_experts=%d outside [1, %d]", L->n_experts, MOE_MAX_EXPERTS);
+    if (L->top_k < 1 || L->top_k > L->n_experts || L->top_k > MOE_MAX_TOPK)
+        return fail(MOE_ESHAPE, "top_k=%d outside [1, min(n_experts, %d)]", L->top_k, MOE_MAX_TOPK);
+    for (int e = 0; e < L->n_experts; ++e) {
+        const moe_expert& x = L->experts[e];
+        if (x.prec != MOE_PREC_FP16 && x.prec != MOE_PREC_INT4G64)
+            return fail(MOE_EINVAL, "expert %d: unknown precision %d", e, x.prec);
+        if (x.resident && x.prec == MOE_PREC_INT4G64 &&
+            (!x.w1.scale || !x.w1.zero || !x.w3.scale || !x.w3.zero || !x.w2.scale || !x.w2.zero))
+            return fail(MOE_EINVAL, "expert %d: 4-bit matrices need scale and zero", e);
+    }
+    return MOE_OK;
+}
+
+bool expert_resident(const moe_expert& x) { return x.resident && x.w1.data && x.w3.data && x.w2.data; }
+
+DevExperts device_table(const moe_layer* L) {
+    DevExperts t;
+    memset(&t, 0, sizeof(t));
+    for (int e = 0; e < L->n_experts; ++e) {
+        const moe_expert& x = L->experts[e];
+        DevExpert& y = t.e[e];
+        y.prec = x.prec;
+        y.resident = expert_resident(x) ? 1 : 0;
+        auto cp = [](const moe_mat& m) { return DevMat{(const uint8_t*)m.data, (const half_t*)m.scale, (const half_t*)m.zero}; };
+        y.w1 = cp(x.w1);
+        y.w3 = cp(x.w3);
+        y.w2 = cp(x.w2);
+    }
+    return t;
+}
+
+int check_ws(const moe_layer* L, int T, void* ws, size_t ws_bytes, Workspace* out) {
+    if (!ws) return fail(MOE_EWORKSPACE, "workspace is NULL");
+    if ((uintptr_t)ws % 256) return fail(MOE_EWORKSPACE, "workspace must be 256-byte aligned");
+    *out = carve_workspace(ws, T, L->d_model, L->d_ff, L->n_experts, L->top_k);
+    if (ws_bytes < out->bytes)
+        return fail(MOE_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, out->bytes);
+    return MOE_OK;
+}
+
+// gating -> grouping -> experts -> weighted average, all on `st`; x may alias nothing in ws except ws.xn.
+int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int T, const half_t* residual,
+               half_t* out, int32_t* idx_out, float* gate_out, const Workspace& w, bool reset_status, hipStream_t st) {
+    const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
+    launch_route(x, (const half_t*)L->w_gate, L->gate_bias, T, d, E, k, w.idx, w.gate, idx_out, gate_out,
+                 reset_status ? w.status : nullptr, st);
+    launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
+    RowMap rows{w.offsets, w.perm, k, -1, 0};
+    launch_ffn_up(table, E, rows, x, d, f, w.h, w.status, st);
+    launch_ffn_down(table, E, rows, w.h, d, f, w.y, w.status, st);
+    launch_combine(w.y, w.gate, w.inv, T, d, k, residual, out, st);
+    return check_hip(st);
+}
+
+}  // namespace
+
+namespace moemix {
+
+namespace {
+struct Trace {
+    int kernel = -1;
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+thread_local Trace g_trace;
+}  // namespace
+
+void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop) { g_trace = Trace{kernel, start, stop}; }
+
+TraceScope::TraceScope(int kernel_, hipStream_t st_) : kernel(kernel_), st(st_) {
+    if (g_trace.kernel == kernel) (void)hipEventRecord(g_trace.start, st);
+}
+
+TraceScope::~TraceScope() {
+    if (g_trace.kernel == kernel) {
+        (void)hipEventRecord(g_trace.stop, st);
+        g_trace.kernel = -1;
+    }
+}
+
+}  // namespace moemix
+
+extern "C" {
+
+int moe_trace_kernel(int kernel, void* start_event, void* stop_event) {
+    if (kernel < 0 || kernel > kKernelRmsnorm || !start_event || !stop_event)
+        return fail(MOE_EINVAL, "moe_trace_kernel: bad kernel id or NULL event");
+    trace_arm(kernel, (hipEvent_t)start_event, (hipEvent_t)stop_event);
+    return MOE_OK;
+}
+
+size_t moe_workspace_bytes(const moe_layer* layer, int n_tokens) {
+    if (!layer || n_tokens < 1 || layer->d_model < 1 || layer->d_ff < 1 || layer->n_experts < 1 || layer->top_k < 1)
+        return 0;
+    return carve_workspace(nullptr, n_tokens, layer->d_model, layer->d_ff, layer->n_experts, layer->top_k).bytes;
+}
+
+int moe_route(const moe_layer* layer, const void* x, int T, int32_t* topk_idx, float* topk_gate, moe_stream_t stream) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!x || !topk_idx || !topk_gate) return fail(MOE_EINVAL, "moe_route: NULL argument");
+    if (T < 1) return fail(MOE_ESHAPE, "moe_route: T=%d < 1", T);
+    launch_route((const half_t*)x, (const half_t*)layer->w_gate, layer->gate_bias, T, layer->d_model, layer->n_experts,
+                 layer->top_k, topk_idx, topk_gate, nullptr, nullptr, nullptr, (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_permute(const moe_layer* layer, const int32_t* topk_idx, int T, int32_t* counts, int32_t* offsets,
+                int32_t* perm, void* ws, size_t ws_bytes, moe_stream_t stream) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!topk_idx || !counts || !offsets || !perm) return fail(MOE_EINVAL, "moe_permute: NULL argument");
+    if (T < 1) return fail(MOE_ESHAPE, "moe_permute: T=%d < 1", T);
+    Workspace w;
+    if (int rc = check_ws(layer, T, ws, ws_bytes, &w)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    launch_zero_words(w.status, 1, st);   // the status word describes this call
+    launch_permute(topk_idx, T * layer->top_k, layer->n_experts, counts, offsets, perm, w.inv, w.status, st);
+    return check_hip(st);
+}
+
+int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows, int n, float* y, void* ws,
+                         size_t ws_bytes, moe_stream_t stream) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!x_rows || !y) return fail(MOE_EINVAL, "moe_expert_ffn_mixed: NULL argument");
+    if (expert < 0 || expert >= layer->n_experts) return fail(MOE_EINVAL, "expert %d outside [0, %d)", expert, layer->n_experts);
+    if (n < 1) return fail(MOE_ESHAPE, "moe_expert_ffn_mixed: n=%d < 1", n);
+    if (!expert_resident(layer->experts[expert])) return fail(MOE_ENOTRESIDENT, "expert %d is not resident", expert);
+    // the hidden rows need n*d_ff halves: a workspace sized for ceil(n / top_k) tokens holds them
+    const int T_equiv = (n + layer->top_k - 1) / layer->top_k;
+    Workspace w;
+    if (int rc = check_ws(layer, T_equiv, ws, ws_bytes, &w)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const DevExperts table = device_table(layer);
+    RowMap rows{nullptr, nullptr, layer->top_k, expert, n};
+    launch_ffn_up(table, layer->n_experts, rows, (const half_t*)x_rows, layer->d_model, layer->d_ff, w.h, w.status, st);
+    launch_ffn_down(table, layer->n_experts, rows, w.h, layer->d_model, layer->d_ff, y, w.status, st);
+    return check_hip(st);
+}
+
+int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, int32_t* topk_idx_out,
+                      float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!x || !out) return fail(MOE_EINVAL, "moe_layer_forward: NULL argument");
+    if (T < 1) return fail(MOE_ESHAPE, "moe_layer_forward: T=%d < 1", T);
+    Workspace w;
+    if (int rc = check_ws(layer, T, ws, ws_bytes, &w)) return rc;
+    const DevExperts table = device_table(layer);
+    return layer_body(layer, table, (const half_t*)x, T, nullptr, (half_t*)out, topk_idx_out, topk_gate_out, w, true,
+                      (hipStream_t)stream);
+}
+
+int moe_chain_forward(const moe_layer* layers, const void* const* rms_gain, int n_layers, float eps, void* h, int T,
+                      int32_t* topk_idx_out, void* ws, size_t ws_bytes, moe_stream_t stream) {
+    if (!layers || !rms_gain || !h) return fail(MOE_EINVAL, "moe_chain_forward: NULL argument");
+    if (n_layers < 1 || T < 1) return fail(MOE_ESHAPE, "moe_chain_forward: n_layers=%d, T=%d", n_layers, T);
+    for (int l = 0; l < n_layers; ++l) {
+        if (int rc = check_layer(&layers[l])) return rc;
+        if (!rms_gain[l]) return fail(MOE_EINVAL, "rms_gain[%d] is NULL", l);
+        if (layers[l].d_model != layers[0].d_model || layers[l].d_ff != layers[0].d_ff ||
+            layers[l].n_experts != layers[0].n_experts || layers[l].top_k != layers[0].top_k)
+            return fail(MOE_ESHAPE, "layer %d differs in shape from layer 0", l);
+    }
+    Workspace w;
+    if (int rc = check_ws(&layers[0], T, ws, ws_bytes, &w)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int d = layers[0].d_model, k = layers[0].top_k;
+    for (int l = 0; l < n_layers; ++l) {
+        const DevExperts table = device_table(&layers[l]);
+        launch_rmsnorm((const half_t*)h, (const half_t*)rms_gain[l], T, d, eps, w.xn, st);
+        int32_t* idx_out = topk_idx_out ? topk_idx_out + (size_t)l * T * k : nullptr;
+        if (int rc = layer_body(&layers[l], table, w.xn, T, (const half_t*)h, (half_t*)h, idx_out, nullptr, w, l == 0, st))
+            return rc;
+    }
+    return MOE_OK;
+}
+
+int moe_dequant_int4(const moe_mat* m, int out, int in, void* w_fp16, moe_stream_t stream) {
+    if (!m || !m->data || !m->scale || !m->zero || !w_fp16) return fail(MOE_EINVAL, "moe_dequant_int4: NULL argument");
+    if (out < 0 || in < 0) return fail(MOE_EINVAL, "moe_dequant_int4: negative size");
+    if (in % MOE_GROUP) return fail(MOE_ESHAPE, "moe_dequant_int4: in=%d not a multiple of %d", in, MOE_GROUP);
+    launch_dequant_int4(DevMat{(const uint8_t*)m->data, (const half_t*)m->scale, (const half_t*)m->zero}, out, in,
+                        (half_t*)w_fp16, (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_quantize_int4(const void* w_fp16, int out, int in, void* packed, void* scale, void* zero, moe_stream_t stream) {
+    if (!w_fp16 || !packed || !scale || !zero) return fail(MOE_EINVAL, "moe_quantize_int4: NULL argument");
+    if (out < 0 || in < 0) return fail(MOE_EINVAL, "moe_quantize_int4: negative size");
+    if (in % MOE_GROUP) return fail(MOE_ESHAPE, "moe_quantize_int4: in=%d not a multiple of %d", in, MOE_GROUP);
+    launch_quantize_int4((const half_t*)w_fp16, out, in, (uint8_t*)packed, (half_t*)scale, (half_t*)zero,
+                         (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_synth_fill_f16(void* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale, int kind,
+                       moe_stream_t stream) {
+    if (!dst && n) return fail(MOE_EINVAL, "moe_synth_fill_f16: NULL destination");
+    if (kind != 0 && kind != 1) return fail(MOE_EINVAL, "moe_synth_fill_f16: kind=%d", kind);
+    launch_synth_fill((half_t*)dst, n, first, seed, stream_id, scale, kind, (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_read_status(void* ws, moe_stream_t stream, int* status_bits) {
+    if (!ws || !status_bits) return fail(MOE_EINVAL, "moe_read_status: NULL argument");
+    int32_t v = 0;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(&v, ws, sizeof(v), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+    *status_bits = v;
+    return MOE_OK;
+}
+
+const char* moe_last_error(void) { return g_err; }
+
+int moe_version(void) { return 1000; }
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Shared device/host declarations of the moemix HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moemix.h"
+
+namespace moemix {
+
+constexpr int kWave = 64;
+constexpr int kGroup = MOE_GROUP;
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+
+// Device-side copy of the expert table, passed by value as a kernel argument (2.5 KB).
+struct DevMat {
+    const uint8_t* data;
+    const half_t* scale;
+    const half_t* zero;
+};
+struct DevExpert {
+    int32_t prec;
+    int32_t resident;
+    DevMat w1, w3, w2;
+};
+struct DevExperts {
+    DevExpert e[MOE_MAX_EXPERTS];
+};
+
+// Status word bits, set by kernels with atomicOr (bit index = -moe_status).
+constexpr int kStatusBadIndex = 1 << 1;
+constexpr int kStatusNotResident = 1 << 3;
+
+// Workspace layout, computed identically by moe_workspace_bytes and the entry points.
+struct Workspace {
+    int32_t* status;    // [64] first word is the status word
+    int32_t* idx;       // [T, k]
+    float* gate;        // [T, k]
+    int32_t* counts;    // [E]
+    int32_t* offsets;   // [E + 1]
+    int32_t* perm;      // [T * k]   grouped row -> flat pair
+    int32_t* inv;       // [T * k]   flat pair -> grouped row (-1: dropped)
+    int32_t* tiles;     // [kMaxTiles * 4] work list of the grouped matrix kernels (+ counter)
+    half_t* xn;         // [T, d]    normed input of the chain
+    half_t* h;          // [T * k, f]  SwiGLU hidden rows, grouped order
+    float* y;           // [T * k, d]  expert outputs, grouped order
+    size_t bytes;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline Workspace carve_workspace(void* base, int T, int d, int f, int E, int k) {
+    Workspace w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = base ? (char*)base + off : nullptr;
+        off += align_up(bytes, 256);
+        return (void*)p;
+    };
+    const size_t P = (size_t)T * k;
+    w.status = (int32_t*)take(64 * sizeof(int32_t));
+    w.idx = (int32_t*)take(P * sizeof(int32_t));
+    w.gate = (float*)take(P * sizeof(float));
+    w.counts = (int32_t*)take((size_t)E * sizeof(int32_t));
+    w.offsets = (int32_t*)take((size_t)(E + 1) * sizeof(int32_t));
+    w.perm = (int32_t*)take(P * sizeof(int32_t));
+    w.inv = (int32_t*)take(P * sizeof(int32_t));
+    w.tiles = (int32_t*)take(256);
+    w.xn = (half_t*)take((size_t)T * d * sizeof(half_t));
+    w.h = (half_t*)take(P * f * sizeof(half_t));
+    w.y = (float*)take(P * d * sizeof(float));
+    w.bytes = off;
+    return w;
+}
+
+// ---------------------------------------------------------------- device helpers
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float silu_mul(float a, float b) { return a / (1.0f + __expf(-a)) * b; }
+
+// Exact dequantized weight: fp16_rne( fp32(q) * fp32(s) + fp32(z) ).  q*s is exact in fp32, so
+// whether the compiler fuses the multiply-add or not the fp32 sum is the same.
+__device__ __forceinline__ half_t dequant_one(uint32_t q, float s, float z) {
+    return (half_t)((float)q * s + z);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace moemix

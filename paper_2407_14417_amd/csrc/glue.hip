@@ -1,0 +1,83 @@
+// 16-bit glue around the expert kernels: weighted average of the selected experts' outputs
+// (paper §1), RMSNorm and residual add of the chained configuration (§3: non-expert parts are
+// always 16-bit).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace moemix {
+
+// out[t, c] = fp16( residual[t, c] + sum_s gate[t, s] * y[inv[t*k+s], c] ), slots added in order.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y, const float* __restrict__ gate,
+                                                       const int32_t* __restrict__ inv, int d, int k,
+                                                       const half_t* __restrict__ residual, half_t* __restrict__ out) {
+    const int t = blockIdx.y;
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < k; ++s) {
+        const int r = inv[t * k + s];
+        if (r < 0) continue;
+        const float g = gate[t * k + s];
+        const float4_t v = *(const float4_t*)(y + (size_t)r * d + c);
+        acc += g * v;
+    }
+    if (residual) {
+        const half4_t rv = *(const half4_t*)(residual + (size_t)t * d + c);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] += (float)rv[j];
+    }
+    half4_t o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (half_t)acc[j];
+    *(half4_t*)(out + (size_t)t * d + c) = o;
+}
+
+void launch_combine(const float* y, const float* gate, const int32_t* inv, int T, int d, int k, const half_t* residual,
+                    half_t* out, hipStream_t st) {
+    TraceScope trace(kKernelCombine, st);
+    dim3 grid((d / 4 + 255) / 256, T);
+    combine_kernel<<<grid, 256, 0, st>>>(y, gate, inv, d, k, residual, out);
+}
+
+// out[t, :] = fp16( h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * g ), one workgroup per token.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const half_t* __restrict__ h, const half_t* __restrict__ g, int d,
+                                                       float eps, half_t* __restrict__ out) {
+    __shared__ float part[4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const half_t* hr = h + (size_t)t * d;
+    float ss = 0.0f;
+    for (int c = tid * 8; c < d; c += 256 * 8) {
+        const half8_t v = *(const half8_t*)(hr + c);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += (float)v[j] * (float)v[j];
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    const float total = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(total / (float)d + eps);
+    for (int c = tid * 8; c < d; c += 256 * 8) {
+        const half8_t v = *(const half8_t*)(hr + c);
+        const half8_t gv = *(const half8_t*)(g + c);
+        half8_t o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (half_t)((float)v[j] * inv * (float)gv[j]);
+        *(half8_t*)(out + (size_t)t * d + c) = o;
+    }
+}
+
+void launch_rmsnorm(const half_t* h, const half_t* g, int T, int d, float eps, half_t* out, hipStream_t st) {
+    TraceScope trace(kKernelRmsnorm, st);
+    rmsnorm_kernel<<<T, 256, 0, st>>>(h, g, d, eps, out);
+}
+
+// Fill kernel used instead of a memset node so that every launch sequence stays graph-capturable.
+__global__ void zero_words_kernel(int32_t* p, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+void launch_zero_words(int32_t* p, int n, hipStream_t st) {
+    if (n > 0) zero_words_kernel<<<(n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024, 256, 0, st>>>(p, n);
+}
+
+}  // namespace moemix

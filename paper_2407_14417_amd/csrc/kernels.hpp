@@ -1,0 +1,61 @@
+// Host-callable launchers of the moemix kernels (internal to the library).
+#pragma once
+
+#include "common.hpp"
+
+namespace moemix {
+
+// How the matrix kernels find their rows.
+//   grouped: rows [offsets[e], offsets[e+1]) of the grouped order belong to expert e; grouped row r
+//            reads token perm[r] / top_k of x.
+//   direct : one given expert, rows 0..n-1 of x in order (moe_expert_ffn_mixed).
+struct RowMap {
+    const int32_t* offsets;  // device [E+1] or nullptr (direct)
+    const int32_t* perm;     // device [P] or nullptr (direct)
+    int top_k;
+    int direct_expert;       // >= 0: direct mode
+    int direct_n;
+};
+
+void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, int d, int E, int k, int32_t* idx,
+                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st);
+void launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                    int32_t* status, hipStream_t st);
+
+// h[r, :] = silu(W1 x_r) * (W3 x_r) for every row of every expert that has rows.
+void launch_ffn_up(const DevExperts& ex, int E, const RowMap& rows, const half_t* x, int d, int f, half_t* h,
+                   int32_t* status, hipStream_t st);
+// y[r, :] = W2 h[r, :]
+void launch_ffn_down(const DevExperts& ex, int E, const RowMap& rows, const half_t* h, int d, int f, float* y,
+                     int32_t* status, hipStream_t st);
+
+// out[t, :] = fp16( (residual ? residual[t, :] : 0) + sum_s gate[t, s] * y[inv[t*k + s], :] )
+void launch_combine(const float* y, const float* gate, const int32_t* inv, int T, int d, int k, const half_t* residual,
+                    half_t* out, hipStream_t st);
+void launch_zero_words(int32_t* p, int n, hipStream_t st);
+void launch_rmsnorm(const half_t* h, const half_t* g, int T, int d, float eps, half_t* out, hipStream_t st);
+
+void launch_dequant_int4(const DevMat& m, int out, int in, half_t* w, hipStream_t st);
+void launch_quantize_int4(const half_t* w, int out, int in, uint8_t* packed, half_t* scale, half_t* zero,
+                          hipStream_t st);
+void launch_synth_fill(half_t* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale, int kind,
+                       hipStream_t st);
+
+}  // namespace moemix
+
+namespace moemix {
+
+// Kernel ids for moe_trace_kernel (same values as MOE_KERNEL_* in the public header).
+enum KernelId { kKernelRoute = 0, kKernelPermute = 1, kKernelUp = 2, kKernelDown = 3, kKernelCombine = 4,
+                kKernelRmsnorm = 5 };
+
+// One-shot event bracket around the next launch of a given kernel on this thread.
+void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop);
+struct TraceScope {
+    int kernel;
+    hipStream_t st;
+    TraceScope(int kernel, hipStream_t st);
+    ~TraceScope();
+};
+
+}  // namespace moemix

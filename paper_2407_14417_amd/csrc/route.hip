@@ -1,0 +1,146 @@
+// Gating network with top-k selection (paper §1, §2.1) and the grouping of (token, slot)
+// pairs by expert.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace moemix {
+
+// One workgroup per token.  Each thread takes 8-column chunks of the token row and of every
+// gate row (one 128-bit load each), accumulates E partial logits in fp32, the partials are
+// summed with wavefront shuffles and a 4-entry LDS step in a fixed order, then lane 0 runs
+// top_k selection passes (strict ">" keeps the lower index among equal logits) and the softmax
+// over the selected logits.
+template <int EMAX>
+__global__ __launch_bounds__(256) void route_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wg,
+                                                     const float* __restrict__ bias, int d, int E, int k,
+                                                     int32_t* __restrict__ idx, float* __restrict__ gate,
+                                                     int32_t* __restrict__ idx2, float* __restrict__ gate2,
+                                                     int32_t* __restrict__ status) {
+    __shared__ float part[4][EMAX];
+    __shared__ float logit[EMAX];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    if (t == 0 && tid == 0 && status) *status = 0;   // status word describes the call that starts here
+    float acc[EMAX];
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) acc[e] = 0.0f;
+    const half_t* xr = x + (size_t)t * d;
+    for (int c = tid * 8; c < d; c += 256 * 8) {
+        const half8_t xv = *(const half8_t*)(xr + c);
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            if (e < E) {
+                const half8_t wv = *(const half8_t*)(wg + (size_t)e * d + c);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[e] += (float)xv[j] * (float)wv[j];
+            }
+        }
+    }
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+        if (e < E) {
+            const float s = wave_sum(acc[e]);
+            if (lane == 0) part[wave][e] = s;
+        }
+    }
+    __syncthreads();
+    if (tid < E) logit[tid] = ((part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid])) + (bias ? bias[tid] : 0.0f);
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t taken = 0;
+        int sel[MOE_MAX_TOPK];
+        float lsel[MOE_MAX_TOPK];
+        for (int s = 0; s < k; ++s) {
+            int best = -1;
+            float lb = 0.0f;
+            for (int e = 0; e < E; ++e) {
+                if (taken & (1u << e)) continue;
+                const float l = logit[e];
+                if (best < 0 || l > lb) { best = e; lb = l; }
+            }
+            taken |= 1u << best;
+            sel[s] = best;
+            lsel[s] = lb;
+        }
+        float u[MOE_MAX_TOPK];
+        float denom = 0.0f;
+        for (int s = 0; s < k; ++s) { u[s] = expf(lsel[s] - lsel[0]); denom += u[s]; }
+        for (int s = 0; s < k; ++s) {
+            const float g = u[s] / denom;
+            idx[(size_t)t * k + s] = sel[s];
+            gate[(size_t)t * k + s] = g;
+            if (idx2) idx2[(size_t)t * k + s] = sel[s];
+            if (gate2) gate2[(size_t)t * k + s] = g;
+        }
+    }
+}
+
+void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, int d, int E, int k, int32_t* idx,
+                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st) {
+    TraceScope trace(kKernelRoute, st);
+    if (E <= 8)
+        route_kernel<8><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+    else
+        route_kernel<MOE_MAX_EXPERTS><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+}
+
+// One workgroup.  Wave w owns experts w, w+16: it walks all pairs in order, 64 at a time, and a
+// ballot + popcount gives every pair routed to its expert a rank in increasing pair order, so the
+// grouping is the unique stable one.
+__global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ idx, int P, int E,
+                                                        int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ inv,
+                                                        int32_t* __restrict__ status) {
+    __shared__ int32_t cnt[MOE_MAX_EXPERTS];
+    __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    for (int e = wave; e < E; e += 16) {
+        int c = 0;
+        for (int i0 = 0; i0 < P; i0 += 64) {
+            const int i = i0 + lane;
+            const int v = (i < P) ? idx[i] : -1;
+            c += __popcll(__ballot(v == e));
+        }
+        if (lane == 0) cnt[e] = c;
+    }
+    // pairs with an index outside [0, E) belong to no expert: flag them
+    for (int i = tid; i < P; i += 1024) {
+        const int v = idx[i];
+        if (v < 0 || v >= E) {
+            inv[i] = -1;
+            atomicOr(status, kStatusBadIndex);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { off[e] = run; run += cnt[e]; }
+        off[E] = run;
+    }
+    __syncthreads();
+    if (tid <= E) offsets[tid] = off[tid];
+    if (tid < E) counts[tid] = cnt[tid];
+    for (int e = wave; e < E; e += 16) {
+        int base = off[e];
+        for (int i0 = 0; i0 < P; i0 += 64) {
+            const int i = i0 + lane;
+            const int v = (i < P) ? idx[i] : -1;
+            const unsigned long long m = __ballot(v == e);
+            if (v == e) {
+                const int r = base + __popcll(m & ((1ull << lane) - 1ull));
+                perm[r] = i;
+                inv[i] = r;
+            }
+            base += __popcll(m);
+        }
+    }
+}
+
+void launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                    int32_t* status, hipStream_t st) {
+    TraceScope trace(kKernelPermute, st);
+    permute_kernel<<<1, 1024, 0, st>>>(idx, P, E, counts, offsets, perm, inv, status);
+}
+
+}  // namespace moemix

@@ -1,0 +1,30 @@
+"""Upload of host workloads (numpy, oracle descriptors) into device descriptors of the binding."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2407_14417_amd import binding as mm
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def device_mat(m) -> mm.Mat:
+    if m.scale is None:
+        return mm.Mat(dev(m.data))
+    return mm.Mat(dev(m.data), dev(m.scale), dev(m.zero))
+
+
+def device_expert(e) -> mm.Expert:
+    if e is None:
+        return mm.Expert(mm.PREC_FP16, None, None, None, resident=False)
+    return mm.Expert(mm.PREC_INT4G64 if e.int4 else mm.PREC_FP16, device_mat(e.w1), device_mat(e.w3),
+                     device_mat(e.w2), resident=e.resident)
+
+
+def device_layer(wl) -> mm.Layer:
+    cfg = wl.cfg
+    bias = None if wl.bias is None else dev(wl.bias)
+    return mm.Layer(cfg.d, cfg.f, cfg.k, dev(wl.wg), [device_expert(e) for e in wl.experts], bias)
