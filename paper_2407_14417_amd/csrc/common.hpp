@@ -94,8 +94,16 @@ __device__ __forceinline__ float silu_mul(float a, float b) { return a / (1.0f +
 
 // Exact dequantized weight: fp16_rne( fp32(q) * fp32(s) + fp32(z) ).  q*s is exact in fp32, so
 // whether the compiler fuses the multiply-add or not the fp32 sum is the same.
+// fp32 -> fp16, round to nearest even, of a value that has already been rounded to fp32.  The empty
+// asm keeps the compiler from folding the producing multiply/add into a mixed-precision instruction
+// that would round the exact result once, straight to fp16 (different on ties).
+__device__ __forceinline__ half_t f32_to_f16_rne(float v) {
+    asm volatile("" : "+v"(v));
+    return (half_t)v;
+}
+
 __device__ __forceinline__ half_t dequant_one(uint32_t q, float s, float z) {
-    return (half_t)((float)q * s + z);
+    return f32_to_f16_rne((float)q * s + z);
 }
 
 #endif  // __HIPCC__

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void quantize_int4_kernel(const half_t* __rest
         mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
     }
     const float range = __fsub_rn(mx, mn);
-    const half_t s16 = (half_t)__fdiv_rn(range, 15.0f);
+    const half_t s16 = f32_to_f16_rne(__fdiv_rn(range, 15.0f));
     const float s = (float)s16;
     uint32_t q = 0;
     if (s != 0.0f) {
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void synth_fill_kernel(half_t* __restrict__ ds
         } else {
             c = 2 * (int32_t)(h0 >> 40) - ((1 << 24) - 1);
         }
-        dst[j] = (half_t)__fmul_rn((float)c, scale);
+        dst[j] = f32_to_f16_rne(__fmul_rn((float)c, scale));
     }
 }
 
