@@ -56,6 +56,9 @@ def lib():
     if _lib is None:
         if not _LIB_PATH.exists():
             raise RuntimeError(f"{_LIB_PATH} is missing: run __graft_entry__.build() (hipcc, gfx950) first")
+        # torch first: its HIP runtime owns the streams and the memory that are passed in, and the library
+        # must bind to that same runtime instance rather than load a second one
+        import torch  # noqa: F401
         L = ctypes.CDLL(str(_LIB_PATH))
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         LP = ctypes.POINTER(CLayer)

@@ -21,9 +21,8 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _host_expert(orc, cfg, e, layer=0):
-    c = common.Config(cfg.name, cfg.d, cfg.f, cfg.E, cfg.k, cfg.T, cfg.int4_experts, seed=cfg.seed, layer=layer)
-    w1, w3, w2 = common.expert_weights_f16(c, e)
+def _host_expert(orc, cfg, e):
+    w1, w3, w2 = common.expert_weights_f16(cfg, e)
     if e in cfg.int4_experts:
         return orc.Expert(orc.quantize_int4(w1), orc.quantize_int4(w3), orc.quantize_int4(w2))
     return orc.Expert(orc.Mat(w1), orc.Mat(w3), orc.Mat(w2))
