@@ -150,31 +150,41 @@ def main() -> int:
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
 
-        # ---- roofline leg: the same steps, eagerly, every launch of the dominant kernel between HIP events
+        # ---- roofline leg: the same steps, eagerly, the two matrix kernels of every step between HIP events
         ev = HipEvents()
-        pairs = [(ev.create(), ev.create()) for _ in range(steps)]
+        traced = {"up": mm.KERNEL_UP, "down": mm.KERNEL_DOWN, "route": mm.KERNEL_ROUTE}
+        pairs = {n: [(ev.create(), ev.create()) for _ in range(steps)] for n in traced}
         for j, i in enumerate(range(warmup, n_tok)):
-            mm.moe_trace_kernel(mm.KERNEL_UP, pairs[j][0], pairs[j][1])
+            for n, kid in traced.items():
+                mm.moe_trace_kernel(kid, pairs[n][j][0], pairs[n][j][1])
             step(i)
         stream.synchronize()
-        up_ms = np.array([ev.elapsed_ms(a, b) for a, b in pairs])
-        for a, b in pairs:
-            ev.destroy(a)
-            ev.destroy(b)
+        ms = {n: np.array([ev.elapsed_ms(a, b) for a, b in pairs[n]]) for n in traced}
+        for n in traced:
+            for a, b in pairs[n]:
+                ev.destroy(a)
+                ev.destroy(b)
 
     idx = idx_all[warmup:].cpu().numpy()
     per_step_bytes = np.array([workload.stored_bytes(layers[(warmup + j) % pool], idx[j]) for j in range(steps)], dtype=np.float64)
-    # up-projection share: w1 and w3 of both routed experts = 2/3 of their stored bytes
+    # up-projection: w1 and w3 of both routed experts = 2/3 of their stored bytes; down-projection: w2 = 1/3
     gate_bytes = E * D * 2
     up_bytes = (per_step_bytes - gate_bytes) * (2.0 / 3.0)
+    down_bytes = (per_step_bytes - gate_bytes) * (1.0 / 3.0)
+    up_ms = ms["up"]
     n_int4 = np.array([sum(int(e) in INT4_EXPERTS for e in idx[j]) for j in range(steps)])
     by_pair = {}
     for kind, name in ((0, "fp16+fp16"), (1, "fp16+int4"), (2, "int4+int4")):
         sel = n_int4 == kind
         if sel.any():
             by_pair[name] = {"launches": int(sel.sum()), "avg_us": float(up_ms[sel].mean() * 1e3),
-                             "GBps": float(up_bytes[sel].sum() / (up_ms[sel].sum() * 1e-3) / 1e9)}
+                             "GBps": float(up_bytes[sel].sum() / (up_ms[sel].sum() * 1e-3) / 1e9),
+                             "down_avg_us": float(ms["down"][sel].mean() * 1e3),
+                             "down_GBps": float(down_bytes[sel].sum() / (ms["down"][sel].sum() * 1e-3) / 1e9)}
     achieved = float(up_bytes.sum() / (up_ms.sum() * 1e-3) / 1e9)
+    other = {"down_projection": {"avg_launch_us": float(ms["down"].mean() * 1e3),
+                                 "GBps": float(down_bytes.sum() / (ms["down"].sum() * 1e-3) / 1e9)},
+             "route": {"avg_launch_us": float(ms["route"].mean() * 1e3)}}
 
     result = {
         "metric": "MoE-layer tokens/s + effective weight HBM GB/s (% of peak), Mixtral shape",
@@ -197,7 +207,8 @@ def main() -> int:
         "pct_of_hbm_peak": float(per_step_bytes.sum() / elapsed / 1e9 / HBM_PEAK_GBPS * 100.0),
         "roofline": {"bound": "hbm", "kernel": "expert up-projection (w1, w3 of both routed experts, SiLU-gate)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "avg_launch_us": float(up_ms.mean() * 1e3), "by_pair": by_pair},
+                     "traffic": None, "avg_launch_us": float(up_ms.mean() * 1e3), "by_pair": by_pair,
+                     "other_kernels": other},
     }
     if args.cpu_tokens > 0:
         result["cpu_baseline"] = cpu_baseline(args.seed, args.cpu_tokens)

@@ -3,6 +3,7 @@
 // moe_read_status.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "common.hpp"
@@ -50,6 +51,22 @@ int check_layer(const moe_layer* L) {
     return MOE_OK;
 }
 
+// Launch shapes that can be overridden from the environment for measurement sweeps.
+struct Tuning {
+    int up_blocks;
+};
+const Tuning& tuning() {
+    static const Tuning t = [] {
+        Tuning v{1024};
+        if (const char* s = getenv("MOEMIX_UP_BLOCKS")) {
+            const int n = atoi(s);
+            if (n >= 1 && n <= 65536) v.up_blocks = n;
+        }
+        return v;
+    }();
+    return t;
+}
+
 bool expert_resident(const moe_expert& x) { return x.resident && x.w1.data && x.w3.data && x.w2.data; }
 
 DevExperts device_table(const moe_layer* L) {
@@ -83,6 +100,12 @@ int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
     launch_route(x, (const half_t*)L->w_gate, L->gate_bias, T, d, E, k, w.idx, w.gate, idx_out, gate_out,
                  reset_status ? w.status : nullptr, st);
+    if (T == 1 && decode_shape_ok(d, f)) {
+        // batch-1 decode: no grouping needed, the weighted average is fused into the down-projection
+        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, tuning().up_blocks, st);
+        launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, residual, out, w.status, st);
+        return check_hip(st);
+    }
     launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
     RowMap rows{w.offsets, w.perm, k, -1, 0};
     launch_ffn_up(table, E, rows, x, d, f, w.h, w.status, st);
@@ -97,22 +120,22 @@ namespace moemix {
 
 namespace {
 struct Trace {
-    int kernel = -1;
+    bool armed = false;
     hipEvent_t start = nullptr, stop = nullptr;
 };
-thread_local Trace g_trace;
+thread_local Trace g_trace[kKernelRmsnorm + 1];   // one slot per kernel id: several kernels of one call can be armed
 }  // namespace
 
-void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop) { g_trace = Trace{kernel, start, stop}; }
+void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop) { g_trace[kernel] = Trace{true, start, stop}; }
 
 TraceScope::TraceScope(int kernel_, hipStream_t st_) : kernel(kernel_), st(st_) {
-    if (g_trace.kernel == kernel) (void)hipEventRecord(g_trace.start, st);
+    if (g_trace[kernel].armed) (void)hipEventRecord(g_trace[kernel].start, st);
 }
 
 TraceScope::~TraceScope() {
-    if (g_trace.kernel == kernel) {
-        (void)hipEventRecord(g_trace.stop, st);
-        g_trace.kernel = -1;
+    if (g_trace[kernel].armed) {
+        (void)hipEventRecord(g_trace[kernel].stop, st);
+        g_trace[kernel].armed = false;
     }
 }
 

@@ -90,6 +90,28 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// ---------------------------------------------------------------- wavefront reduction on the DPP network
+
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, true));
+}
+
+// Sum over the 64 lanes; the total is returned to every lane through a scalar register.
+__device__ __forceinline__ float wave_total(float v) {
+    v += dpp_move<0xB1>(v);          // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);          // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);         // row_half_mirror
+    v += dpp_move<0x140>(v);         // row_mirror: every lane of a row of 16 holds the row sum
+    v += dpp_move<0x142, 0xA>(v);    // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xC>(v);    // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// Reinterpret a 32-bit word as two halves.  The argument is taken by value on purpose: the bit-cast
+// builtin applied directly to an element of a vector lvalue (v[j]) reads element 0 whatever j is.
+__device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
+
 __device__ __forceinline__ float silu_mul(float a, float b) { return a / (1.0f + __expf(-a)) * b; }
 
 // Exact dequantized weight: fp16_rne( fp32(q) * fp32(s) + fp32(z) ).  q*s is exact in fp32, so

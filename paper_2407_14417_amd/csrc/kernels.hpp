@@ -29,6 +29,13 @@ void launch_ffn_up(const DevExperts& ex, int E, const RowMap& rows, const half_t
 void launch_ffn_down(const DevExperts& ex, int E, const RowMap& rows, const half_t* h, int d, int f, float* y,
                      int32_t* status, hipStream_t st);
 
+// Batch-1 decode path (one token): shapes it covers, and its two kernels.
+bool decode_shape_ok(int d, int f);
+void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
+                      int32_t* status, int blocks, hipStream_t st);
+void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
+                        int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st);
+
 // out[t, :] = fp16( (residual ? residual[t, :] : 0) + sum_s gate[t, s] * y[inv[t*k + s], :] )
 void launch_combine(const float* y, const float* gate, const int32_t* inv, int T, int d, int k, const half_t* residual,
                     half_t* out, hipStream_t st);

@@ -11,28 +11,32 @@ namespace moemix {
 // top_k selection passes (strict ">" keeps the lower index among equal logits) and the softmax
 // over the selected logits.
 template <int EMAX>
-__global__ __launch_bounds__(256) void route_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wg,
+__global__ __launch_bounds__(512) void route_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wg,
                                                      const float* __restrict__ bias, int d, int E, int k,
                                                      int32_t* __restrict__ idx, float* __restrict__ gate,
                                                      int32_t* __restrict__ idx2, float* __restrict__ gate2,
                                                      int32_t* __restrict__ status) {
-    __shared__ float part[4][EMAX];
+    __shared__ float part[8][EMAX];
     __shared__ float logit[EMAX];
     const int t = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, n_waves = blockDim.x >> 6;
     if (t == 0 && tid == 0 && status) *status = 0;   // status word describes the call that starts here
     float acc[EMAX];
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) acc[e] = 0.0f;
     const half_t* xr = x + (size_t)t * d;
-    for (int c = tid * 8; c < d; c += 256 * 8) {
-        const half8_t xv = *(const half8_t*)(xr + c);
+    for (int c = tid * 8; c < d; c += blockDim.x * 8) {
+        const uint4_t xv = *(const uint4_t*)(xr + c);
+        uint4_t wv[EMAX];
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e)
+            if (e < E) wv[e] = *(const uint4_t*)(wg + (size_t)e * d + c);
 #pragma unroll
         for (int e = 0; e < EMAX; ++e) {
             if (e < E) {
-                const half8_t wv = *(const half8_t*)(wg + (size_t)e * d + c);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[e] += (float)xv[j] * (float)wv[j];
+                for (int j = 0; j < 4; ++j)
+                    acc[e] = __builtin_amdgcn_fdot2(as_half2(xv[j]), as_half2(wv[e][j]), acc[e], false);
             }
         }
     }
@@ -40,12 +44,16 @@ __global__ __launch_bounds__(256) void route_kernel(const half_t* __restrict__ x
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) {
         if (e < E) {
-            const float s = wave_sum(acc[e]);
+            const float s = wave_total(acc[e]);
             if (lane == 0) part[wave][e] = s;
         }
     }
     __syncthreads();
-    if (tid < E) logit[tid] = ((part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid])) + (bias ? bias[tid] : 0.0f);
+    if (tid < E) {
+        float s = 0.0f;
+        for (int w = 0; w < n_waves; ++w) s += part[w][tid];
+        logit[tid] = s + (bias ? bias[tid] : 0.0f);
+    }
     __syncthreads();
     if (tid == 0) {
         uint32_t taken = 0;
@@ -79,10 +87,12 @@ __global__ __launch_bounds__(256) void route_kernel(const half_t* __restrict__ x
 void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, int d, int E, int k, int32_t* idx,
                   float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st) {
     TraceScope trace(kKernelRoute, st);
+    int threads = (d / 8 + 63) / 64 * 64;      // one 8-column chunk per thread when the row fits
+    threads = threads < 64 ? 64 : (threads > 512 ? 512 : threads);
     if (E <= 8)
-        route_kernel<8><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+        route_kernel<8><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
     else
-        route_kernel<MOE_MAX_EXPERTS><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+        route_kernel<MOE_MAX_EXPERTS><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
 }
 
 // One workgroup.  Wave w owns experts w, w+16: it walks all pairs in order, 64 at a time, and a

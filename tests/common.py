@@ -105,6 +105,8 @@ PREFILL = Config("prefill", 4096, 14336, 8, 2, 512, (2, 3, 4, 5, 6, 7), zipf=1.2
 # d and f are not multiples of the kernels' larger tiles, T*k/E is ragged.
 MEDIUM = Config("medium", 1024, 2816, 8, 2, 24, (1, 2, 5, 7))
 MEDIUM_ZIPF = Config("medium_zipf", 1024, 2816, 8, 2, 96, (2, 3, 4, 5, 6, 7), zipf=1.2)
+# Smallest shape the batch-1 decode kernels take (d and f multiples of 2048), with a precision mix.
+DECODE_SMALL = Config("decode_small", 2048, 4096, 8, 2, 1, (1, 2, 5, 7))
 
 
 def gate_matrix(cfg: Config) -> np.ndarray:

@@ -148,7 +148,7 @@ def test_chain_32_layers_decode(orc):
     resident).  The oracle regenerates only the routed experts.  Teacher-forced per layer; the free-running
     trajectory is compared up to the first layer whose top-3 logit gap is below 1e-2."""
     d, f, E, k, L, eps = 4096, 14336, 8, 2, 32, 1e-5
-    seed = 0
+    seed = 1          # first seed whose oracle trajectory keeps every top-3 logit gap above 1e-2 (found on the CPU)
     mask = synth.precision_mask(E * L, E * L // 2, seed)
     layers, host_cfgs = [], []
     for l in range(L):

@@ -356,3 +356,61 @@ def test_chain_teacher_forced_and_free_running(orc, cfg, n_layers):
     assert mm.moe_read_status(ws) == 0
     assert np.array_equal(idx_out.cpu().numpy()[:, safe_tok], np.stack(idxs)[:, safe_tok])
     assert_ffn_close(h.cpu().numpy()[safe_tok], hs[-1][safe_tok], "free-running h")
+
+
+# ---------------------------------------------------------------- batch-1 decode kernels at a small shape
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_decode_path_small_shape_all_precision_mixes(orc, k):
+    """T=1 goes through the decode kernels (token in registers, factored 4-bit dot products, fused weighted
+    average).  Twelve tokens: with 4 of 8 experts 4-bit the routed sets cover 16-bit only, mixed and 4-bit only."""
+    base = common.DECODE_SMALL
+    cfg = common.Config(base.name, base.d, base.f, base.E, k, 1, base.int4_experts)
+    wl = build_workload(cfg, orc)
+    layer = device_layer(wl)
+    ws = mm.alloc_workspace(layer, 1)
+    kinds = set()
+    for retry in range(12):
+        x = synth.normal_f16((1, cfg.d), 1.0, cfg.seed, synth.x_stream(retry))
+        lg = np.sort(common.logits_f64(x, wl.wg, None)[0])[::-1]
+        if (lg[:k] - lg[1:k + 1]).min() < 1e-3:
+            continue
+        _say(f"decode small k={k} token stream {retry}")
+        out = torch.empty((1, cfg.d), dtype=torch.float16, device="cuda")
+        idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        gate = torch.empty((1, k), dtype=torch.float32, device="cuda")
+        mm.moe_layer_forward(layer, dev(x), out, ws, idx, gate)
+        assert mm.moe_read_status(ws) == 0
+        ref, ref_idx, ref_gate = orc.layer_forward(x, wl.wg, wl.experts, k)
+        assert np.array_equal(idx.cpu().numpy(), ref_idx)
+        assert np.allclose(gate.cpu().numpy(), ref_gate, rtol=0, atol=GATE_ATOL)
+        assert_ffn_close(out.cpu().numpy(), ref, f"decode small k={k} retry={retry}")
+        kinds.add(tuple(sorted(int(e) in cfg.int4_experts for e in ref_idx[0])))
+    assert len(kinds) >= (3 if k == 2 else 2)
+
+
+def test_decode_path_non_resident_and_chain(orc):
+    cfg = common.DECODE_SMALL
+    wl = build_workload(cfg, orc)
+    x = synth.normal_f16((1, cfg.d), 1.0, cfg.seed, synth.x_stream(0))
+    ref_idx, ref_gate = orc.route(x, wl.wg, cfg.k)
+    layer = device_layer(wl)
+    layer.experts[int(ref_idx[0, 1])].resident = False
+    layer = mm.Layer(cfg.d, cfg.f, cfg.k, layer.w_gate, layer.experts)
+    out, idx, gate, status = _run_layer(layer, x, cfg)
+    assert status == mm.STATUS_NOT_RESIDENT and np.array_equal(idx, ref_idx)
+    ref = float(ref_gate[0, 0]) * orc.expert_ffn(wl.experts[int(ref_idx[0, 0])], x)
+    assert_ffn_close(out, ref, "decode, one expert left out")
+    # three chained blocks at this shape: RMSNorm -> decode kernels with the residual fused into the down-projection
+    eps, g = 1e-5, np.ones(cfg.d, dtype=np.float16)
+    wls = _chain_workloads(cfg, orc, 3)
+    hs, idxs, gap = _oracle_trajectory(orc, wls, x, g, eps, cfg.k)
+    assert gap[0] > 1e-2, "pick another token stream"
+    layers = [device_layer(w) for w in wls]
+    h = dev(x)
+    idx_out = torch.empty((3, 1, cfg.k), dtype=torch.int32, device="cuda")
+    ws = mm.alloc_workspace(layers[0], 1)
+    mm.moe_chain_forward(mm.Chain(layers, [dev(g)] * 3), eps, h, ws, idx_out)
+    assert mm.moe_read_status(ws) == 0
+    assert np.array_equal(idx_out.cpu().numpy(), np.stack(idxs))
+    assert_ffn_close(h.cpu().numpy(), hs[-1], "decode chain")
