@@ -39,17 +39,31 @@ __device__ __forceinline__ void load_act_i4(const half_t* __restrict__ src, ActI
     a.c2 = se + so;
 }
 
+// (a & mask) | bits in one instruction.  The compiler keeps two instructions here because the fused form
+// may read only one scalar operand: the mask goes in a scalar register, the OR-ed bits in a vector one.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits));
+    return r;
+}
+
+__device__ __forceinline__ uint32_t bias_magic() {
+    uint32_t m;
+    asm("v_mov_b32 %0, 0x64006400" : "=v"(m));   // not volatile: identical copies are merged and hoisted
+    return m;
+}
+
 // s * sum_c q_c x_c + z * sum_c x_c over the lane's 32 columns of one row.
 __device__ __forceinline__ float dot_i4(const uint4_t pk, const ActI4& a, float s, float z) {
-    constexpr uint32_t kMagic = 0x64006400u;   // fp16 pair (1024, 1024)
+    const uint32_t magic = bias_magic();   // fp16 pair (1024, 1024), held in a vector register
     float lo = 0.0f, hi = 0.0f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t w = pk[j], w8 = w >> 8;
-        const half2_t q04 = as_half2((w & 0x000F000Fu) | kMagic);    // 1024 + q
-        const half2_t q15 = as_half2((w & 0x00F000F0u) | kMagic);    // 1024 + 16 q
-        const half2_t q26 = as_half2((w8 & 0x000F000Fu) | kMagic);
-        const half2_t q37 = as_half2((w8 & 0x00F000F0u) | kMagic);
+        const half2_t q04 = as_half2(and_or(w, 0x000F000Fu, magic));    // 1024 + q
+        const half2_t q15 = as_half2(and_or(w, 0x00F000F0u, magic));    // 1024 + 16 q
+        const half2_t q26 = as_half2(and_or(w8, 0x000F000Fu, magic));
+        const half2_t q37 = as_half2(and_or(w8, 0x00F000F0u, magic));
         lo = __builtin_amdgcn_fdot2(q04, a.p[j][0], lo, false);
         hi = __builtin_amdgcn_fdot2(q15, a.p[j][1], hi, false);
         lo = __builtin_amdgcn_fdot2(q26, a.p[j][2], lo, false);
@@ -76,35 +90,70 @@ __device__ __forceinline__ float dot_f16(const uint4_t w, const ActF16& a, float
     return acc;
 }
 
-__device__ __forceinline__ uint4_t load_stream(const void* p) {
-    return __builtin_nontemporal_load((const uint4_t*)p);
+// Pointers into device (global) memory, typed as such: after the register pin below the compiler can no
+// longer infer the address space by itself and would fall back to generic (flat) loads.
+#define MOEMIX_GLOBAL __attribute__((address_space(1)))
+typedef const char MOEMIX_GLOBAL* gptr_t;
+
+// Pins a uniform pointer in a scalar register pair at this point.  Without it the loop optimizer turns
+// "row base + lane offset" into per-lane 64-bit pointer recurrences, one vector register pair per load.
+__device__ __forceinline__ gptr_t scalar_ptr(const void* p) {
+    gptr_t g = (gptr_t)p;
+    asm volatile("" : "+s"(g));
+    return g;
 }
+
+// Uniform base pointer + 32-bit per-lane byte offset: compiles to the scalar-base addressing form, so a
+// whole set of loads shares one offset register instead of one 64-bit address register pair each.
+__device__ __forceinline__ gptr_t at(gptr_t uniform_base, uint32_t lane_offset_bytes) {
+    return uniform_base + lane_offset_bytes;
+}
+
+__device__ __forceinline__ uint4_t load_stream(gptr_t p) {
+    return __builtin_nontemporal_load((const uint4_t MOEMIX_GLOBAL*)p);
+}
+
+__device__ __forceinline__ half_t load_half(gptr_t p) { return *(const half_t MOEMIX_GLOBAL*)p; }
+
+// Index of the wavefront inside its workgroup, as a scalar (the compiler cannot see that
+// threadIdx.x >> 6 is the same for all 64 lanes).
+__device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
 
 // ---------------------------------------------------------------- up-projection
 
 // Rows of all routed slots are laid end to end, weighted by their stored bytes (9 units per 4-bit row
 // pair, 32 per 16-bit one), and cut into equal shares, one per wavefront: every wavefront streams the
 // same number of bytes whatever the precision mix.
+constexpr int kUpRowsI4 = 2;   // rows per register buffer of the 4-bit path
+
 template <int NCH>   // d_model / 2048
-__global__ __launch_bounds__(256) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
+__global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
                                                          const half_t* __restrict__ x, int f, int k,
                                                          half_t* __restrict__ h, int32_t* status) {
     constexpr int d = NCH * 2048;
     const int lane = threadIdx.x & 63;
-    const long n_waves = (long)gridDim.x * 4, gw = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    long total = 0;
-    for (int s = 0; s < k; ++s) total += (long)f * (ex.e[idx[s]].prec == MOE_PREC_INT4G64 ? 9 : 32);
-    const long lo = total * gw / n_waves, hi = total * (gw + 1) / n_waves;
-    long base = 0;
+    // 32-bit arithmetic throughout: total <= 8 slots * 16384 rows * 32 units
+    // the wavefront index goes through a scalar register: everything derived from it (row ranges, row base
+    // addresses) is then uniform, and the loads below take the scalar-base + 32-bit lane-offset form
+    const uint32_t n_waves = gridDim.x * 4, gw = blockIdx.x * 4 + wave_index();
+    uint32_t total = 0;
+    for (int s = 0; s < k; ++s) total += (uint32_t)f * (ex.e[idx[s]].prec == MOE_PREC_INT4G64 ? 9u : 32u);
+    // balanced cut: the first (total % n_waves) wavefronts take one unit more
+    const uint32_t share = total / n_waves, extra = total % n_waves;
+    const uint32_t lo = gw * share + (gw < extra ? gw : extra);
+    const uint32_t hi = lo + share + (gw < extra ? 1u : 0u);
+    uint32_t base = 0;
     for (int s = 0; s < k; ++s) {
         const DevExpert& ee = ex.e[idx[s]];
         const bool int4 = ee.prec == MOE_PREC_INT4G64;
-        const long cost = int4 ? 9 : 32;
-        // rows whose first cost unit falls in [lo, hi)
-        long r0 = (lo - base + cost - 1) / cost, r1 = (hi - base + cost - 1) / cost;
-        r0 = r0 < 0 ? 0 : (r0 > f ? f : r0);
-        r1 = r1 < 0 ? 0 : (r1 > f ? f : r1);
-        base += (long)f * cost;
+        const uint32_t span = (uint32_t)f * (int4 ? 9u : 32u);
+        // rows whose first cost unit falls in [lo, hi): ceil((lo - base) / cost) .. ceil((hi - base) / cost)
+        const uint32_t l = lo > base ? (lo - base < span ? lo - base : span) : 0u;
+        const uint32_t u = hi > base ? (hi - base < span ? hi - base : span) : 0u;
+        // (the divisions run on the vector unit; move the uniform results back to scalar registers)
+        const int r0 = __builtin_amdgcn_readfirstlane((int)(int4 ? (l + 8u) / 9u : (l + 31u) / 32u));
+        const int r1 = __builtin_amdgcn_readfirstlane((int)(int4 ? (u + 8u) / 9u : (u + 31u) / 32u));
+        base += span;
         if (r0 >= r1) continue;
         if (!ee.resident || !ee.w1.data) {
             if (lane == 0) atomicOr(status, kStatusNotResident);
@@ -116,37 +165,64 @@ __global__ __launch_bounds__(256) void decode_up_kernel(DevExperts ex, const int
 #pragma unroll
             for (int c = 0; c < NCH; ++c) load_act_i4(x + c * 2048 + lane * 32, act[c]);
             constexpr int gpr = d / 64;
-            const uint8_t* q1 = ee.w1.data + lane * 16;
-            const uint8_t* q3 = ee.w3.data + lane * 16;
-            const half_t *s1 = ee.w1.scale + (lane >> 1), *z1 = ee.w1.zero + (lane >> 1);
-            const half_t *s3 = ee.w3.scale + (lane >> 1), *z3 = ee.w3.zero + (lane >> 1);
-            for (long r = r0; r < r1; r += 2) {
-                uint4_t pk1[2][NCH], pk3[2][NCH];
-                half_t sc1[2][NCH], zr1[2][NCH], sc3[2][NCH], zr3[2][NCH];
+            constexpr int RB = kUpRowsI4;
+            const uint32_t lane_q = lane * 16, lane_g = (lane >> 1) * 2;   // byte offsets inside a row
+            struct Rows {
+                uint4_t pk1[RB][NCH], pk3[RB][NCH];
+                half_t sc1[RB][NCH], zr1[RB][NCH], sc3[RB][NCH], zr3[RB][NCH];
+            };
+            // RB rows starting at r; rows past the end repeat the last one (loaded, never stored)
+            auto load_rows = [&](Rows& B, int r) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const long row = (r + i < r1) ? r + i : r1 - 1;
+                for (int i = 0; i < RB; ++i) {
+                    const int row = (r + i < r1) ? r + i : r1 - 1;
+                    const gptr_t q1 = scalar_ptr(ee.w1.data + (size_t)row * (d / 2));      // uniform row bases
+                    const gptr_t q3 = scalar_ptr(ee.w3.data + (size_t)row * (d / 2));
+                    const gptr_t s1 = scalar_ptr(ee.w1.scale + (size_t)row * gpr);
+                    const gptr_t z1 = scalar_ptr(ee.w1.zero + (size_t)row * gpr);
+                    const gptr_t s3 = scalar_ptr(ee.w3.scale + (size_t)row * gpr);
+                    const gptr_t z3 = scalar_ptr(ee.w3.zero + (size_t)row * gpr);
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) {
-                        pk1[i][c] = load_stream(q1 + row * (d / 2) + c * 1024);
-                        pk3[i][c] = load_stream(q3 + row * (d / 2) + c * 1024);
-                        sc1[i][c] = s1[row * gpr + c * 32];
-                        zr1[i][c] = z1[row * gpr + c * 32];
-                        sc3[i][c] = s3[row * gpr + c * 32];
-                        zr3[i][c] = z3[row * gpr + c * 32];
+                        B.pk1[i][c] = load_stream(at(q1, lane_q + c * 1024));
+                        B.pk3[i][c] = load_stream(at(q3, lane_q + c * 1024));
+                        B.sc1[i][c] = load_half(at(s1, lane_g + c * 64));
+                        B.zr1[i][c] = load_half(at(z1, lane_g + c * 64));
+                        B.sc3[i][c] = load_half(at(s3, lane_g + c * 64));
+                        B.zr3[i][c] = load_half(at(z3, lane_g + c * 64));
                     }
                 }
+            };
+            auto compute_rows = [&](const Rows& B, int r) {
+                float am = 0.0f, bm = 0.0f;   // lane i keeps the totals of row r + i
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < RB; ++i) {
                     float a = 0.0f, b = 0.0f;
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) {
-                        a += dot_i4(pk1[i][c], act[c], (float)sc1[i][c], (float)zr1[i][c]);
-                        b += dot_i4(pk3[i][c], act[c], (float)sc3[i][c], (float)zr3[i][c]);
+                        a += dot_i4(B.pk1[i][c], act[c], (float)B.sc1[i][c], (float)B.zr1[i][c]);
+                        b += dot_i4(B.pk3[i][c], act[c], (float)B.sc3[i][c], (float)B.zr3[i][c]);
                     }
                     a = wave_total(a);
                     b = wave_total(b);
-                    if (lane == 0 && r + i < r1) hs[r + i] = (half_t)silu_mul(a, b);
+                    am = lane == i ? a : am;
+                    bm = lane == i ? b : bm;
+                }
+                if (lane < RB && r + lane < r1) hs[r + lane] = (half_t)silu_mul(am, bm);
+            };
+            // two register buffers: the loads of the next rows are in flight while the current ones are used
+            Rows A, B;
+            load_rows(A, r0);
+            for (int r = r0; r < r1; r += 2 * RB) {
+                if (r + RB < r1) load_rows(B, r + RB);
+                __builtin_amdgcn_sched_barrier(0);
+                compute_rows(A, r);
+                __builtin_amdgcn_sched_barrier(0);
+                if (r + RB < r1) {
+                    if (r + 2 * RB < r1) load_rows(A, r + 2 * RB);
+                    __builtin_amdgcn_sched_barrier(0);
+                    compute_rows(B, r + RB);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         } else {
@@ -154,24 +230,39 @@ __global__ __launch_bounds__(256) void decode_up_kernel(DevExperts ex, const int
             ActF16 act[NL];
 #pragma unroll
             for (int c = 0; c < NL; ++c) load_act_f16(x + c * 512 + lane * 8, act[c]);
-            const half_t* w1 = (const half_t*)ee.w1.data + lane * 8;
-            const half_t* w3 = (const half_t*)ee.w3.data + lane * 8;
-            for (long r = r0; r < r1; ++r) {
-                uint4_t v1[NL], v3[NL];
+            const uint8_t* w1 = ee.w1.data;
+            const uint8_t* w3 = ee.w3.data;
+            const uint32_t lane_w = lane * 16;
+            // one register buffer = one matrix row (w1 and w3 rows alternate between the two buffers)
+            struct Row {
+                uint4_t v[NL];
+            };
+            auto load_row = [&](Row& B, const uint8_t* w, int r) {
+                const gptr_t rowp = scalar_ptr(w + (size_t)r * (d * 2));   // uniform row base
 #pragma unroll
-                for (int c = 0; c < NL; ++c) {
-                    v1[c] = load_stream(w1 + r * d + c * 512);
-                    v3[c] = load_stream(w3 + r * d + c * 512);
-                }
-                float a = 0.0f, b = 0.0f;
+                for (int c = 0; c < NL; ++c) B.v[c] = load_stream(at(rowp, lane_w + c * 1024));
+            };
+            auto dot_row = [&](const Row& B) {
+                float a0 = 0.0f, a1 = 0.0f;
 #pragma unroll
-                for (int c = 0; c < NL; ++c) {
-                    a = dot_f16(v1[c], act[c], a);
-                    b = dot_f16(v3[c], act[c], b);
+                for (int c = 0; c < NL; c += 2) {
+                    a0 = dot_f16(B.v[c], act[c], a0);
+                    a1 = dot_f16(B.v[c + 1], act[c + 1], a1);
                 }
-                a = wave_total(a);
-                b = wave_total(b);
+                return wave_total(a0 + a1);
+            };
+            Row A, B;
+            load_row(A, w1, r0);
+            for (int r = r0; r < r1; ++r) {
+                load_row(B, w3, r);
+                __builtin_amdgcn_sched_barrier(0);
+                const float a = dot_row(A);
+                __builtin_amdgcn_sched_barrier(0);
+                if (r + 1 < r1) load_row(A, w1, r + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const float b = dot_row(B);
                 if (lane == 0) hs[r] = (half_t)silu_mul(a, b);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -179,10 +270,12 @@ __global__ __launch_bounds__(256) void decode_up_kernel(DevExperts ex, const int
 
 // ---------------------------------------------------------------- down-projection + weighted average
 
-// One workgroup per 8 output rows; wavefront w owns columns [2048 w, 2048 w + 2048) of every row, for
-// every slot in turn, with that slice of the slot's hidden row in registers.  Partial sums meet in LDS
-// and are added in wavefront order, so the result does not depend on scheduling.
-constexpr int kDownRows = 8;
+// One workgroup per kDownRows output rows; wavefront w owns columns [2048 w, 2048 w + 2048) of every row,
+// for every slot in turn, with that slice of the slot's hidden row in registers.  Rows go through two
+// register buffers of kDownBatch rows, so the next batch is in flight while the current one is used.
+// Partial sums meet in LDS and are added in wavefront order: the result does not depend on scheduling.
+constexpr int kDownRows = 16;
+constexpr int kDownBatch = 4;
 
 __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const int32_t* __restrict__ idx,
                                                            const float* __restrict__ gate,
@@ -190,7 +283,8 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
                                                            const half_t* __restrict__ residual,
                                                            half_t* __restrict__ out, int32_t* status) {
     __shared__ float part[8][kDownRows];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+    const uint32_t wave = wave_index();
     const int row0 = blockIdx.x * kDownRows;
     float acc[kDownRows];
 #pragma unroll
@@ -206,47 +300,91 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
         if (ee.prec == MOE_PREC_INT4G64) {
             ActI4 act;
             load_act_i4(hs + lane * 32, act);
-            const int gpr = f >> 6;
-            const uint8_t* q = ee.w2.data + (size_t)row0 * (f >> 1) + wave * 1024 + lane * 16;
-            const half_t* sc = ee.w2.scale + (size_t)row0 * gpr + wave * 32 + (lane >> 1);
-            const half_t* zr = ee.w2.zero + (size_t)row0 * gpr + wave * 32 + (lane >> 1);
-            uint4_t pk[kDownRows];
-            half_t sv[kDownRows], zv[kDownRows];
+            const size_t gpr = f >> 6, qpr = f >> 1;
+            const uint8_t* q = ee.w2.data + (size_t)row0 * qpr + wave * 1024;        // uniform
+            const half_t* sc = ee.w2.scale + (size_t)row0 * gpr + wave * 32;
+            const half_t* zr = ee.w2.zero + (size_t)row0 * gpr + wave * 32;
+            const uint32_t lane_q = lane * 16, lane_g = (lane >> 1) * 2;
+            struct Batch {
+                uint4_t pk[kDownBatch];
+                half_t sv[kDownBatch], zv[kDownBatch];
+            };
+            auto load_batch = [&](Batch& B, int rb) {
 #pragma unroll
-            for (int r = 0; r < kDownRows; ++r) {
-                pk[r] = load_stream(q + (size_t)r * (f >> 1));
-                sv[r] = sc[(size_t)r * gpr];
-                zv[r] = zr[(size_t)r * gpr];
+                for (int r = 0; r < kDownBatch; ++r) {
+                    B.pk[r] = load_stream(at(scalar_ptr(q + (size_t)(rb + r) * qpr), lane_q));
+                    B.sv[r] = load_half(at(scalar_ptr(sc + (size_t)(rb + r) * gpr), lane_g));
+                    B.zv[r] = load_half(at(scalar_ptr(zr + (size_t)(rb + r) * gpr), lane_g));
+                }
+            };
+            Batch A, B;
+            load_batch(A, 0);
+#pragma unroll
+            for (int rb = 0; rb < kDownRows; rb += 2 * kDownBatch) {
+                load_batch(B, rb + kDownBatch);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < kDownBatch; ++r)
+                    acc[rb + r] = fmaf(g, dot_i4(A.pk[r], act, (float)A.sv[r], (float)A.zv[r]), acc[rb + r]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rb + 2 * kDownBatch < kDownRows) load_batch(A, rb + 2 * kDownBatch);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < kDownBatch; ++r)
+                    acc[rb + kDownBatch + r] =
+                        fmaf(g, dot_i4(B.pk[r], act, (float)B.sv[r], (float)B.zv[r]), acc[rb + kDownBatch + r]);
+                __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int r = 0; r < kDownRows; ++r) acc[r] = fmaf(g, dot_i4(pk[r], act, (float)sv[r], (float)zv[r]), acc[r]);
         } else {
             ActF16 act[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) load_act_f16(hs + c * 512 + lane * 8, act[c]);
-            const half_t* w = (const half_t*)ee.w2.data + (size_t)row0 * f + wave * 2048 + lane * 8;
+            const uint8_t* w = ee.w2.data + ((size_t)row0 * f + wave * 2048) * 2;       // uniform
+            const uint32_t lane_w = lane * 16;
+            struct Batch {
+                uint4_t v[2][4];     // two rows, four 128-bit loads each
+            };
+            auto load_batch = [&](Batch& B, int rb) {
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const gptr_t rowp = scalar_ptr(w + (size_t)(rb + r) * f * 2);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) B.v[r][c] = load_stream(at(rowp, lane_w + c * 1024));
+                }
+            };
+            auto use_batch = [&](const Batch& B, int rb) {
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    float p0 = 0.0f, p1 = 0.0f;
+                    p0 = dot_f16(B.v[r][0], act[0], p0);
+                    p1 = dot_f16(B.v[r][1], act[1], p1);
+                    p0 = dot_f16(B.v[r][2], act[2], p0);
+                    p1 = dot_f16(B.v[r][3], act[3], p1);
+                    acc[rb + r] = fmaf(g, p0 + p1, acc[rb + r]);
+                }
+            };
+            Batch A, B;
+            load_batch(A, 0);
 #pragma unroll
             for (int rb = 0; rb < kDownRows; rb += 4) {
-                uint4_t v[4][4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) v[r][c] = load_stream(w + (size_t)(rb + r) * f + c * 512);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float p = 0.0f;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) p = dot_f16(v[r][c], act[c], p);
-                    acc[rb + r] = fmaf(g, p, acc[rb + r]);
-                }
+                load_batch(B, rb + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                use_batch(A, rb);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rb + 4 < kDownRows) load_batch(A, rb + 4);
+                __builtin_amdgcn_sched_barrier(0);
+                use_batch(B, rb + 2);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
+    float mine = 0.0f;    // lane r keeps the total of row r
 #pragma unroll
     for (int r = 0; r < kDownRows; ++r) {
         const float t = wave_total(acc[r]);
-        if (lane == 0) part[wave][r] = t;
+        mine = lane == r ? t : mine;
     }
+    if (lane < kDownRows) part[wave][lane] = mine;
     __syncthreads();
     if (threadIdx.x < kDownRows) {
         const int row = row0 + threadIdx.x;
