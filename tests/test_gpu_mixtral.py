@@ -198,6 +198,13 @@ def test_chain_32_layers_decode(orc):
             _say(f"chain: oracle through layer {l}, gap {gap:.3e}")
     _say(f"chain: first layer with a top-3 gap below 1e-2: {first_unsafe}")
     if first_unsafe is None:
-        assert_ffn_close(h_dev, hs[-1], "free-running chain")
+        # Free-running bar.  Each block, fed the oracle's own input, meets the per-block bar above.  Left to
+        # run, block l sees the deviations of blocks 0..l-1 on its input; the residual path carries them on
+        # with unit gain and the L per-block deviations are independent, so they add in quadrature: the bar
+        # on the final hidden state is sqrt(L) times the per-block one (routing must still agree everywhere).
+        max_frac, rel_l2 = common.ffn_errors(h_dev, hs[-1])
+        _say(f"chain: free-running max|err|/max|ref|={max_frac:.3e} relL2={rel_l2:.3e}")
+        grow = float(np.sqrt(L))
+        assert max_frac <= common.MAX_ERR_FRAC * grow and rel_l2 <= common.REL_L2 * grow
     else:
         assert first_unsafe >= 4, "seed gives too short a comparable prefix; pick another seed"
