@@ -53,18 +53,46 @@ int check_layer(const moe_layer* L) {
 
 // Launch shapes that can be overridden from the environment for measurement sweeps.
 struct Tuning {
-    int up_blocks;
+    int up_blocks;   // MOEMIX_UP_BLOCKS: workgroups of the batch-1 up-projection
+    bool no_mfma;    // MOEMIX_NO_MFMA=1: multi-row calls take the shape-agnostic kernels (A/B timing)
+    int mfma_ct;     // MOEMIX_MFMA_CT: 16-row activation tiles per chunk (1, 2, 4, 8), 0 = planned from the shape
+    int mfma_splits; // MOEMIX_MFMA_SPLITS: contraction splits of the down-projection, 0 = planned
 };
 const Tuning& tuning() {
     static const Tuning t = [] {
-        Tuning v{1024};
+        Tuning v{1024, false, 0, 0};
         if (const char* s = getenv("MOEMIX_UP_BLOCKS")) {
             const int n = atoi(s);
             if (n >= 1 && n <= 65536) v.up_blocks = n;
         }
+        if (const char* s = getenv("MOEMIX_NO_MFMA")) v.no_mfma = atoi(s) != 0;
+        if (const char* s = getenv("MOEMIX_MFMA_CT")) {
+            const int n = atoi(s);
+            if (n == 1 || n == 2 || n == 4 || n == 8) v.mfma_ct = n;
+        }
+        if (const char* s = getenv("MOEMIX_MFMA_SPLITS")) {
+            const int n = atoi(s);
+            if (n >= 1 && n <= 16) v.mfma_splits = n;
+        }
         return v;
     }();
     return t;
+}
+
+// Which kernels serve T tokens of a block: T == 1 the batch-1 kernels, otherwise the matrix-core path when
+// the shape allows it, else the shape-agnostic kernels.
+bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff) && !tuning().no_mfma; }
+
+MfmaPlan plan_for(const moe_layer* L, int rows) {
+    MfmaPlan p = plan_mfma(rows, L->d_model, L->d_ff, L->n_experts);
+    if (tuning().mfma_ct) p.ct = tuning().mfma_ct;
+    if (tuning().mfma_splits && (L->d_ff / 128) % tuning().mfma_splits == 0) p.down_splits = tuning().mfma_splits;
+    return p;
+}
+
+int y_splits_for(const moe_layer* L, int T) {
+    if (!use_mfma(L, T * L->top_k)) return 1;
+    return plan_for(L, T * L->top_k).down_splits;
 }
 
 bool expert_resident(const moe_expert& x) { return x.resident && x.w1.data && x.w3.data && x.w2.data; }
@@ -88,7 +116,7 @@ DevExperts device_table(const moe_layer* L) {
 int check_ws(const moe_layer* L, int T, void* ws, size_t ws_bytes, Workspace* out) {
     if (!ws) return fail(MOE_EWORKSPACE, "workspace is NULL");
     if ((uintptr_t)ws % 256) return fail(MOE_EWORKSPACE, "workspace must be 256-byte aligned");
-    *out = carve_workspace(ws, T, L->d_model, L->d_ff, L->n_experts, L->top_k);
+    *out = carve_workspace(ws, T, L->d_model, L->d_ff, L->n_experts, L->top_k, y_splits_for(L, T));
     if (ws_bytes < out->bytes)
         return fail(MOE_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, out->bytes);
     return MOE_OK;
@@ -108,9 +136,17 @@ int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int
     }
     launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
     RowMap rows{w.offsets, w.perm, k, -1, 0};
-    launch_ffn_up(table, E, rows, x, d, f, w.h, w.status, st);
-    launch_ffn_down(table, E, rows, w.h, d, f, w.y, w.status, st);
-    launch_combine(w.y, w.gate, w.inv, T, d, k, residual, out, st);
+    const size_t split_stride = (size_t)T * k * d;
+    if (use_mfma(L, T * k)) {
+        const MfmaPlan p = plan_for(L, T * k);
+        launch_ffn_up_mfma(table, E, rows, T * k, x, d, f, w.h, p.ct, w.status, st);
+        launch_ffn_down_mfma(table, E, rows, T * k, w.h, d, f, w.y, p.ct, p.down_splits, split_stride, w.status, st);
+        launch_combine(w.y, p.down_splits, split_stride, w.gate, w.inv, T, d, k, residual, out, st);
+    } else {
+        launch_ffn_up(table, E, rows, x, d, f, w.h, w.status, st);
+        launch_ffn_down(table, E, rows, w.h, d, f, w.y, w.status, st);
+        launch_combine(w.y, 1, split_stride, w.gate, w.inv, T, d, k, residual, out, st);
+    }
     return check_hip(st);
 }
 
@@ -153,7 +189,7 @@ int moe_trace_kernel(int kernel, void* start_event, void* stop_event) {
 size_t moe_workspace_bytes(const moe_layer* layer, int n_tokens) {
     if (!layer || n_tokens < 1 || layer->d_model < 1 || layer->d_ff < 1 || layer->n_experts < 1 || layer->top_k < 1)
         return 0;
-    return carve_workspace(nullptr, n_tokens, layer->d_model, layer->d_ff, layer->n_experts, layer->top_k).bytes;
+    return carve_workspace(nullptr, n_tokens, layer->d_model, layer->d_ff, layer->n_experts, layer->top_k, y_splits_for(layer, n_tokens)).bytes;
 }
 
 int moe_route(const moe_layer* layer, const void* x, int T, int32_t* topk_idx, float* topk_gate, moe_stream_t stream) {
@@ -192,8 +228,16 @@ int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows,
     hipStream_t st = (hipStream_t)stream;
     const DevExperts table = device_table(layer);
     RowMap rows{nullptr, nullptr, layer->top_k, expert, n};
-    launch_ffn_up(table, layer->n_experts, rows, (const half_t*)x_rows, layer->d_model, layer->d_ff, w.h, w.status, st);
-    launch_ffn_down(table, layer->n_experts, rows, w.h, layer->d_model, layer->d_ff, y, w.status, st);
+    const int d = layer->d_model, f = layer->d_ff;
+    if (use_mfma(layer, n)) {
+        int ct = plan_mfma(n, d, f, 1).ct;        // all n rows belong to the one expert
+        if (tuning().mfma_ct) ct = tuning().mfma_ct;
+        launch_ffn_up_mfma(table, layer->n_experts, rows, n, (const half_t*)x_rows, d, f, w.h, ct, w.status, st);
+        launch_ffn_down_mfma(table, layer->n_experts, rows, n, w.h, d, f, y, ct, 1, 0, w.status, st);
+    } else {
+        launch_ffn_up(table, layer->n_experts, rows, (const half_t*)x_rows, d, f, w.h, w.status, st);
+        launch_ffn_down(table, layer->n_experts, rows, w.h, d, f, y, w.status, st);
+    }
     return check_hip(st);
 }
 

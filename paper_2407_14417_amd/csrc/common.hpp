@@ -51,13 +51,14 @@ struct Workspace {
     int32_t* tiles;     // [kMaxTiles * 4] work list of the grouped matrix kernels (+ counter)
     half_t* xn;         // [T, d]    normed input of the chain
     half_t* h;          // [T * k, f]  SwiGLU hidden rows, grouped order
-    float* y;           // [T * k, d]  expert outputs, grouped order
+    float* y;           // [y_splits][T * k, d]  expert outputs, grouped order, one partial per contraction split
+    int y_splits;
     size_t bytes;
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline Workspace carve_workspace(void* base, int T, int d, int f, int E, int k) {
+inline Workspace carve_workspace(void* base, int T, int d, int f, int E, int k, int y_splits = 1) {
     Workspace w;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -76,7 +77,8 @@ inline Workspace carve_workspace(void* base, int T, int d, int f, int E, int k) 
     w.tiles = (int32_t*)take(256);
     w.xn = (half_t*)take((size_t)T * d * sizeof(half_t));
     w.h = (half_t*)take(P * f * sizeof(half_t));
-    w.y = (float*)take(P * d * sizeof(float));
+    w.y = (float*)take((size_t)y_splits * P * d * sizeof(float));
+    w.y_splits = y_splits;
     w.bytes = off;
     return w;
 }

@@ -1,0 +1,409 @@
+// Expert feed-forward layers on many rows (prefill, batched decode): grouped matrix products on the
+// matrix cores (paper §1: experts are parallel FF layers; §3: each is 16-bit or 4-bit).
+//
+//   up  : h[r, n] = silu(sum_c W1[n,c] x_r[c]) * (sum_c W3[n,c] x_r[c])      rows r of one expert, grouped order
+//   down: y[s][r, n] = sum_{c in split s} W2[n,c] h[r,c]                      partial sums of the contraction splits
+//
+// One workgroup = 4 wavefronts = one (expert, tile of weight rows, chunk of <= 16*CT activation rows, split).
+// Weights are the A operand of v_mfma_f32_16x16x32_f16 and go from device memory straight into registers, in
+// operand layout: lane (r, c) holds 8 contraction elements of weight row r, so a wavefront's load touches 64
+// contiguous bytes of each of 16 rows, and no weight is ever written to LDS.  4-bit weights are loaded as 32
+// codes per lane and expanded in registers (codes masked into the mantissa of an fp16 constant, the constant
+// subtracted, one packed fp16 multiply-add with the group's scale and zero).  Activations are the B operand:
+// a [16*CT, 128] tile per step of the contraction, double-buffered in LDS and shared by the 4 wavefronts.
+// Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one activation row, so
+// results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace moemix {
+
+namespace {
+
+constexpr int kKTile = 128;                 // contraction elements per LDS tile
+constexpr int kLdsRow = kKTile * 2 + 16;    // bytes per activation row in LDS: 16 bytes of padding spread the banks
+
+struct MfmaArgs {
+    DevExperts ex;
+    const int32_t* offsets;   // [E+1] grouped rows per expert, or null in direct mode
+    const int32_t* perm;      // up, grouped: grouped row -> flat pair (token = pair / top_k); null: rows in order
+    int top_k;
+    int direct_expert, direct_n;
+    const half_t* in;         // up: x [T, K]; down: h [rows, K]
+    void* out;                // up: h [rows, N] fp16; down: y [splits][rows_total, N] fp32
+    int K, N, E;
+    int k_per_split;          // contraction elements per split (multiple of 128)
+    size_t split_stride;      // elements of y between two splits
+    int32_t* status;
+};
+
+__device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight 4-bit codes of one word -> their dequantized fp16 values, in the order (0,4,1,5,2,6,3,7).
+__device__ __forceinline__ half8_t expand_word(uint32_t w, half2_t s2, half2_t z2) {
+    const half2_t k1024 = {(half_t)1024.0f, (half_t)1024.0f}, k64 = {(half_t)64.0f, (half_t)64.0f};
+    const uint32_t w8 = w >> 8;
+    // low nibbles land in the mantissa of 1024 (ulp 1), high nibbles in the mantissa of 64 (ulp 1/16, code << 4)
+    const half2_t q04 = as_half2((w & 0x000F000Fu) | 0x64006400u) - k1024;
+    const half2_t q15 = as_half2((w & 0x00F000F0u) | 0x54005400u) - k64;
+    const half2_t q26 = as_half2((w8 & 0x000F000Fu) | 0x64006400u) - k1024;
+    const half2_t q37 = as_half2((w8 & 0x00F000F0u) | 0x54005400u) - k64;
+    const half2_t a = __builtin_elementwise_fma(q04, s2, z2), b = __builtin_elementwise_fma(q15, s2, z2);
+    const half2_t c = __builtin_elementwise_fma(q26, s2, z2), d = __builtin_elementwise_fma(q37, s2, z2);
+    return half8_t{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
+// What one workgroup works on, set up once by the kernel and handed to the precision-specific body.
+struct TileCtx {
+    const half_t* in;        // activations
+    const int32_t* perm;     // up, grouped: grouped row -> flat pair; else null
+    int top_k;
+    int K, N;
+    int begin, m0, rows;     // grouped rows [begin + m0, begin + m0 + rows)
+    int n0;                  // first weight row of the workgroup
+    int k_begin, n_steps;    // contraction range [k_begin, k_begin + 128 n_steps)
+    int mc;                  // rows per LDS buffer (16 * ct of the launch)
+    uint8_t* lds;
+};
+
+// UP: two matrices (w1, w3), 2 tiles of 16 weight rows per wavefront (workgroup: 128 rows);
+// down: one matrix (w2), 4 tiles per wavefront (workgroup: 256 rows).  Either way 4 A operands per step.
+// NCT = 16-row activation tiles computed (a power of two >= the tiles that hold rows; the rest is zeros), so
+// the inner loops are straight-line code the compiler can software-pipeline.
+template <bool UP, bool INT4, int NCT>
+__device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
+    constexpr int NA = 4;
+    const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, c4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = c.K, N = c.N, n_steps = c.n_steps;
+    constexpr int NT = UP ? 128 : 256;
+
+    // ---- activation rows this thread stages: rows tid/16 + 16 i, 16-byte piece tid%16 of each 256-byte row slice
+    const int piece = tid & 15;
+    const half_t* xrow[NCT];
+#pragma unroll
+    for (int i = 0; i < NCT; ++i) {
+        const int rr = (tid >> 4) + 16 * i;
+        if (rr < c.rows) {
+            const int g = c.begin + c.m0 + rr;
+            const size_t src = (UP && c.perm) ? (size_t)(c.perm[g] / c.top_k) : (size_t)g;
+            xrow[i] = c.in + src * K + c.k_begin + piece * 8;
+        } else {
+            xrow[i] = nullptr;
+        }
+    }
+    uint4_t xr[NCT];
+    auto load_x = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) xr[i] = xrow[i] ? *(const uint4_t*)(xrow[i] + step * kKTile) : uint4_t{0, 0, 0, 0};
+    };
+    auto store_x = [&](int buf) {
+        uint8_t* base = c.lds + buf * (c.mc * kLdsRow) + (tid >> 4) * kLdsRow + piece * 16;
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) {
+            uint4_t v = xr[i];
+            if (INT4) {   // element order (0,4,1,5,2,6,3,7) inside each group of 8, as expand_word delivers codes
+                const half8_t h = __builtin_bit_cast(half8_t, v);
+                v = __builtin_bit_cast(uint4_t, half8_t{h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]});
+            }
+            *(uint4_t*)(base + i * 16 * kLdsRow) = v;
+        }
+    };
+
+    // ---- weight rows of this lane: the wavefront owns NT/4 rows from n0 + wave * NT/4, in tiles of 16
+    const uint8_t* wdata[NA];
+    const half_t* wscale[NA];
+    const half_t* wzero[NA];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
+        const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
+        row = row < N ? row : N - 1;                               // rows past the end are loaded from the last row, never stored
+        if (INT4) {
+            wdata[t] = m.data + (size_t)row * (K >> 1) + (c.k_begin >> 1) + c4 * 16;
+            wscale[t] = m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6);
+            wzero[t] = m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6);
+        } else {
+            wdata[t] = m.data + ((size_t)row * K + c.k_begin + c4 * 8) * 2;
+            wscale[t] = wzero[t] = nullptr;
+        }
+    }
+
+    float4_t acc[NA][NCT];
+#pragma unroll
+    for (int t = 0; t < NA; ++t)
+#pragma unroll
+        for (int j = 0; j < NCT; ++j) acc[t][j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // B operand of activation tile j, sub-step s: lane (r16, c4) reads 8 elements of activation row 16 j + r16
+    const int b_lane = r16 * kLdsRow + (INT4 ? c4 * 64 : c4 * 16);
+    constexpr int b_step = INT4 ? 16 : 64;
+
+    // Pipeline, per 128-column step: the activation tile of step+1 is written to the other LDS buffer at the
+    // top of the step (its loads were issued a step earlier), the loads of step+2 are issued, weights run three
+    // steps (4-bit) or three 32-column sub-steps (16-bit) ahead in a ring of four register buffers, and one
+    // barrier closes the step.
+    if (INT4) {
+        const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of the 128-column step
+        uint4_t raw[4][NA];
+        uint32_t sz_cur[NA][2], sz_next[NA][2];
+        // scales and zeros of four steps with one load: lane (r16, c4) fetches the pair of groups of step 4 S + c4
+        auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
+            int step = 4 * S + c4;
+            step = step < n_steps ? step : n_steps - 1;
+#pragma unroll
+            for (int t = 0; t < NA; ++t) {
+                dst[t][0] = *(const uint32_t*)(wscale[t] + step * 2);
+                dst[t][1] = *(const uint32_t*)(wzero[t] + step * 2);
+            }
+        };
+        auto load_w = [&](int slot, int step) {
+#pragma unroll
+            for (int t = 0; t < NA; ++t) raw[slot][t] = *(const uint4_t*)(wdata[t] + step * (kKTile / 2));
+        };
+        auto compute = [&](int slot, int xbuf, int j) {
+            const uint8_t* xb = c.lds + xbuf * (c.mc * kLdsRow) + b_lane;
+            half2_t s2[NA], z2[NA];
+            const int src = (r16 + 16 * j) * 4;     // the lane of this row that fetched step j of the four
+#pragma unroll
+            for (int t = 0; t < NA; ++t) {
+                const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][0]);
+                const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][1]);
+                s2[t] = as_half2(__builtin_amdgcn_perm(sd, sd, sel));
+                z2[t] = as_half2(__builtin_amdgcn_perm(zd, zd, sel));
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                half8_t af[NA];
+#pragma unroll
+                for (int t = 0; t < NA; ++t) af[t] = expand_word(raw[slot][t][s], s2[t], z2[t]);
+#pragma unroll
+                for (int j2 = 0; j2 < NCT; ++j2) {
+                    const half8_t b = *(const half8_t*)(xb + j2 * 16 * kLdsRow + s * b_step);
+#pragma unroll
+                    for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(af[t], b, acc[t][j2]);
+                }
+            }
+        };
+        load_x(0);
+        load_sz(sz_cur, 0);
+        load_w(0, 0);
+        if (1 < n_steps) load_w(1, 1);
+        if (2 < n_steps) load_w(2, 2);
+        store_x(0);
+        if (1 < n_steps) load_x(1);
+        __syncthreads();
+        for (int S = 0; 4 * S < n_steps; ++S) {
+            if (4 * (S + 1) < n_steps) load_sz(sz_next, S + 1);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int step = 4 * S + j;
+                if (step < n_steps) {
+                    if (step + 1 < n_steps) store_x((j + 1) & 1);
+                    if (step + 2 < n_steps) load_x(step + 2);
+                    if (step + 3 < n_steps) load_w((j + 3) & 3, step + 3);
+                    compute(j, j & 1, j);
+                    __syncthreads();
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+        }
+    } else {
+        uint4_t wf[4][NA];
+        auto load_w = [&](int slot, int sub) {   // sub = sub-step index over the whole contraction range (32 columns each)
+#pragma unroll
+            for (int t = 0; t < NA; ++t) wf[slot][t] = *(const uint4_t*)(wdata[t] + sub * 64);
+        };
+        auto compute_sub = [&](int slot, int xbuf, int s) {
+            const uint8_t* xb = c.lds + xbuf * (c.mc * kLdsRow) + b_lane;
+#pragma unroll
+            for (int j2 = 0; j2 < NCT; ++j2) {
+                const half8_t b = *(const half8_t*)(xb + j2 * 16 * kLdsRow + s * b_step);
+#pragma unroll
+                for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, wf[slot][t]), b, acc[t][j2]);
+            }
+        };
+        const int n_sub = n_steps * 4;
+        load_x(0);
+        load_w(0, 0);
+        load_w(1, 1);
+        load_w(2, 2);
+        store_x(0);
+        if (1 < n_steps) load_x(1);
+        __syncthreads();
+        for (int step = 0; step < n_steps; ++step) {
+            if (step + 1 < n_steps) store_x((step + 1) & 1);
+            if (step + 2 < n_steps) load_x(step + 2);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int sub = step * 4 + s;
+                if (sub + 3 < n_sub) load_w((s + 3) & 3, sub + 3);
+                compute_sub(s, step & 1, s);
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- results: lane (r16, c4) holds, for activation row 16 j + r16, weight rows 16 tile + 4 c4 + (0..3)
+#pragma unroll
+    for (int j = 0; j < NCT; ++j) {
+        const int rr = 16 * j + r16;
+        if (rr < c.rows) {
+            const size_t g = (size_t)(c.begin + c.m0 + rr);
+            if (UP) {
+                half_t* h = (half_t*)out_base + g * N;
+#pragma unroll
+                for (int tile = 0; tile < 2; ++tile) {
+                    const int col = c.n0 + wave * 32 + tile * 16 + c4 * 4;
+                    if (col < N) {
+                        half4_t o;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[v] = (half_t)silu_mul(acc[2 * tile][j][v], acc[2 * tile + 1][j][v]);
+                        *(half4_t*)(h + col) = o;
+                    }
+                }
+            } else {
+                float* y = (float*)out_base + g * N;
+#pragma unroll
+                for (int tile = 0; tile < 4; ++tile) {
+                    const int col = c.n0 + wave * 64 + tile * 16 + c4 * 4;
+                    if (col < N) *(float4_t*)(y + col) = acc[tile][j];
+                }
+            }
+        }
+    }
+}
+
+template <bool UP, int CT>
+__global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
+    constexpr int MC = 16 * CT;                  // activation rows per chunk
+    constexpr int NT = UP ? 128 : 256;           // weight rows per workgroup
+    extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][kLdsRow]
+    const int tid = threadIdx.x;
+
+    // ---- which expert, which rows
+    int e, begin, cnt, chunk = blockIdx.y;
+    if (a.direct_expert >= 0) {
+        e = a.direct_expert; begin = 0; cnt = a.direct_n;
+    } else {
+        e = -1; begin = 0; cnt = 0;
+        for (int i = 0; i < a.E; ++i) {
+            const int b = a.offsets[i], n = a.offsets[i + 1] - b, nch = (n + MC - 1) / MC;
+            if (chunk < nch) { e = i; begin = b; cnt = n; break; }
+            chunk -= nch;
+        }
+        if (e < 0) return;
+    }
+    TileCtx c;
+    c.m0 = chunk * MC;
+    if (c.m0 >= cnt) return;
+    c.in = a.in; c.perm = a.perm; c.top_k = a.top_k; c.K = a.K; c.N = a.N;
+    c.begin = begin;
+    c.rows = min(MC, cnt - c.m0);
+    c.n0 = blockIdx.x * NT;
+    c.k_begin = blockIdx.z * a.k_per_split;
+    c.n_steps = a.k_per_split / kKTile;
+    c.mc = MC;
+    c.lds = lds;
+    const DevExpert& ee = a.ex.e[e];
+    void* out_base = UP ? a.out : (void*)((float*)a.out + blockIdx.z * a.split_stride);
+    if (!(ee.resident && ee.w1.data && ee.w3.data && ee.w2.data)) {
+        if (tid == 0 && blockIdx.x == 0) atomicOr(a.status, kStatusNotResident);
+        if (!UP) {   // rows of an expert that cannot run contribute nothing
+            float* y = (float*)out_base;
+            for (int i = tid; i < c.rows * NT; i += 256) {
+                const int rr = i / NT, cc = c.n0 + i % NT;
+                if (cc < c.N) y[(size_t)(begin + c.m0 + rr) * c.N + cc] = 0.0f;
+            }
+        }
+        return;
+    }
+    const bool int4 = ee.prec == MOE_PREC_INT4G64;
+    const int nct = (c.rows + 15) >> 4;          // 16-row tiles that hold any rows
+    if (CT >= 8 && nct > 4) {
+        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT)>(c, ee, out_base);
+    } else if (CT >= 4 && nct > 2) {
+        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT)>(c, ee, out_base);
+    } else if (CT >= 2 && nct > 1) {
+        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT)>(c, ee, out_base);
+    } else {
+        if (int4) tile_body<UP, true, 1>(c, ee, out_base); else tile_body<UP, false, 1>(c, ee, out_base);
+    }
+}
+
+template <bool UP, int CT>
+void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
+    const size_t lds_bytes = 2u * 16 * CT * kLdsRow;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds_bytes);
+        configured = true;
+    }
+    grouped_mfma_kernel<UP, CT><<<grid, 256, lds_bytes, st>>>(a);
+}
+
+template <bool UP>
+void launch_ct(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
+    switch (ct) {
+        case 1: launch_one<UP, 1>(a, grid, st); break;
+        case 2: launch_one<UP, 2>(a, grid, st); break;
+        case 4: launch_one<UP, 4>(a, grid, st); break;
+        default: launch_one<UP, 8>(a, grid, st); break;
+    }
+}
+
+int chunk_slots(const RowMap& rows, int P, int E, int ct) {
+    const int mc = 16 * ct;
+    if (rows.direct_expert >= 0) return (rows.direct_n + mc - 1) / mc;
+    // every expert may end with one ragged chunk
+    const int full = P / mc + E;
+    return full;
+}
+
+}  // namespace
+
+bool mfma_shape_ok(int d, int f) { return d % kKTile == 0 && f % kKTile == 0; }
+
+MfmaPlan plan_mfma(int P, int d, int f, int E) {
+    MfmaPlan p;
+    const int avg = (P + E - 1) / E;              // rows per expert if the load were even
+    p.ct = avg <= 16 ? 1 : avg <= 32 ? 2 : avg <= 64 ? 4 : 8;
+    // down-projection: split the contraction until there are enough workgroups for 256 compute units
+    const int steps = f / kKTile;
+    const int base = ((d + 255) / 256) * (P / (16 * p.ct) + 1);
+    int best = 1;
+    for (int s = 1; s <= 16; ++s)
+        if (steps % s == 0 && base * s <= 1024) best = s;
+    p.down_splits = best;
+    return p;
+}
+
+void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, const half_t* x, int d, int f, half_t* h,
+                        int ct, int32_t* status, hipStream_t st) {
+    TraceScope trace(kKernelUp, st);
+    MfmaArgs a;
+    a.ex = ex; a.offsets = rows.offsets; a.perm = rows.perm; a.top_k = rows.top_k;
+    a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
+    a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
+    dim3 grid((f + 127) / 128, chunk_slots(rows, P, E, ct), 1);
+    launch_ct<true>(a, ct, grid, st);
+}
+
+void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, const half_t* h, int d, int f, float* y,
+                          int ct, int splits, size_t split_stride, int32_t* status, hipStream_t st) {
+    TraceScope trace(kKernelDown, st);
+    MfmaArgs a;
+    a.ex = ex; a.offsets = rows.offsets; a.perm = nullptr; a.top_k = rows.top_k;
+    a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
+    a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
+    a.status = status;
+    dim3 grid((d + 255) / 256, chunk_slots(rows, P, E, ct), splits);
+    launch_ct<false>(a, ct, grid, st);
+}
+
+}  // namespace moemix

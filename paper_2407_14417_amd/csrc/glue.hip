@@ -6,10 +6,11 @@
 
 namespace moemix {
 
-// out[t, c] = fp16( residual[t, c] + sum_s gate[t, s] * y[inv[t*k+s], c] ), slots added in order.
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y, const float* __restrict__ gate,
-                                                       const int32_t* __restrict__ inv, int d, int k,
-                                                       const half_t* __restrict__ residual, half_t* __restrict__ out) {
+// out[t, c] = fp16( residual[t, c] + sum_s gate[t, s] * sum_p y[p][inv[t*k+s], c] ), slots and partials added in order.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y, int splits, size_t split_stride,
+                                                       const float* __restrict__ gate, const int32_t* __restrict__ inv,
+                                                       int d, int k, const half_t* __restrict__ residual,
+                                                       half_t* __restrict__ out) {
     const int t = blockIdx.y;
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= d) return;
@@ -18,7 +19,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
         const int r = inv[t * k + s];
         if (r < 0) continue;
         const float g = gate[t * k + s];
-        const float4_t v = *(const float4_t*)(y + (size_t)r * d + c);
+        float4_t v = *(const float4_t*)(y + (size_t)r * d + c);
+        for (int p = 1; p < splits; ++p) v += *(const float4_t*)(y + p * split_stride + (size_t)r * d + c);
         acc += g * v;
     }
     if (residual) {
@@ -32,11 +34,26 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     *(half4_t*)(out + (size_t)t * d + c) = o;
 }
 
-void launch_combine(const float* y, const float* gate, const int32_t* inv, int T, int d, int k, const half_t* residual,
-                    half_t* out, hipStream_t st) {
+void launch_combine(const float* y, int splits, size_t split_stride, const float* gate, const int32_t* inv, int T, int d,
+                    int k, const half_t* residual, half_t* out, hipStream_t st) {
     TraceScope trace(kKernelCombine, st);
     dim3 grid((d / 4 + 255) / 256, T);
-    combine_kernel<<<grid, 256, 0, st>>>(y, gate, inv, d, k, residual, out);
+    combine_kernel<<<grid, 256, 0, st>>>(y, splits, split_stride, gate, inv, d, k, residual, out);
+}
+
+__global__ __launch_bounds__(256) void reduce_splits_kernel(float* __restrict__ y, int splits, size_t split_stride, size_t n4) {
+    for (size_t i = blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        float4_t v = ((const float4_t*)y)[i];
+        for (int p = 1; p < splits; ++p) v += *(const float4_t*)(y + p * split_stride + i * 4);
+        ((float4_t*)y)[i] = v;
+    }
+}
+
+void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, hipStream_t st) {
+    if (splits < 2 || n == 0) return;
+    const size_t n4 = n / 4;
+    const int blocks = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
+    reduce_splits_kernel<<<blocks, 256, 0, st>>>(y, splits, split_stride, n4);
 }
 
 // out[t, :] = fp16( h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * g ), one workgroup per token.

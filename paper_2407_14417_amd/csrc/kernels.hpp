@@ -29,6 +29,20 @@ void launch_ffn_up(const DevExperts& ex, int E, const RowMap& rows, const half_t
 void launch_ffn_down(const DevExperts& ex, int E, const RowMap& rows, const half_t* h, int d, int f, float* y,
                      int32_t* status, hipStream_t st);
 
+// Matrix-core path for many rows (contraction lengths multiples of 128).  `ct` = 16-row activation tiles per
+// chunk (1, 2, 4 or 8); the down-projection splits the contraction `splits` ways and writes one partial
+// y per split (`split_stride` elements apart), which launch_combine adds up.
+struct MfmaPlan {
+    int ct;
+    int down_splits;
+};
+bool mfma_shape_ok(int d, int f);
+MfmaPlan plan_mfma(int P, int d, int f, int E);
+void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, const half_t* x, int d, int f, half_t* h,
+                        int ct, int32_t* status, hipStream_t st);
+void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, const half_t* h, int d, int f, float* y,
+                          int ct, int splits, size_t split_stride, int32_t* status, hipStream_t st);
+
 // Batch-1 decode path (one token): shapes it covers, and its two kernels.
 bool decode_shape_ok(int d, int f);
 void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
@@ -36,9 +50,12 @@ void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x,
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
                         int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st);
 
-// out[t, :] = fp16( (residual ? residual[t, :] : 0) + sum_s gate[t, s] * y[inv[t*k + s], :] )
-void launch_combine(const float* y, const float* gate, const int32_t* inv, int T, int d, int k, const half_t* residual,
-                    half_t* out, hipStream_t st);
+// out[t, :] = fp16( (residual ? residual[t, :] : 0) + sum_s gate[t, s] * sum_p y[p][inv[t*k + s], :] ),
+// p over the `splits` partial results, `split_stride` elements apart.
+void launch_combine(const float* y, int splits, size_t split_stride, const float* gate, const int32_t* inv, int T, int d,
+                    int k, const half_t* residual, half_t* out, hipStream_t st);
+// y[r, :] = sum_p y[p][r, :] for r < n (in place, into the first partial)
+void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, hipStream_t st);
 void launch_zero_words(int32_t* p, int n, hipStream_t st);
 void launch_rmsnorm(const half_t* h, const half_t* g, int T, int d, float eps, half_t* out, hipStream_t st);
 
