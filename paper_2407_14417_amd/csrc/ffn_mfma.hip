@@ -80,24 +80,24 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     const int K = c.K, N = c.N, n_steps = c.n_steps;
     constexpr int NT = UP ? 128 : 256;
 
-    // ---- activation rows this thread stages: rows tid/16 + 16 i, 16-byte piece tid%16 of each 256-byte row slice
+    // ---- activation rows this thread stages: rows tid/16 + 16 i, 16-byte piece tid%16 of each 256-byte row slice.
+    // Rows past the end of the chunk repeat its last row: their products are computed and never stored.
     const int piece = tid & 15;
     const half_t* xrow[NCT];
 #pragma unroll
     for (int i = 0; i < NCT; ++i) {
-        const int rr = (tid >> 4) + 16 * i;
-        if (rr < c.rows) {
-            const int g = c.begin + c.m0 + rr;
-            const size_t src = (UP && c.perm) ? (size_t)(c.perm[g] / c.top_k) : (size_t)g;
-            xrow[i] = c.in + src * K + c.k_begin + piece * 8;
-        } else {
-            xrow[i] = nullptr;
-        }
+        int rr = (tid >> 4) + 16 * i;
+        rr = rr < c.rows ? rr : c.rows - 1;
+        const int g = c.begin + c.m0 + rr;
+        const size_t src = (UP && c.perm) ? (size_t)(c.perm[g] / c.top_k) : (size_t)g;
+        xrow[i] = c.in + src * K + c.k_begin + piece * 8;
     }
+    const int last = n_steps - 1;    // loads that would run past the contraction range repeat the last step instead
     uint4_t xr[NCT];
     auto load_x = [&](int step) {
+        step = step < last ? step : last;
 #pragma unroll
-        for (int i = 0; i < NCT; ++i) xr[i] = xrow[i] ? *(const uint4_t*)(xrow[i] + step * kKTile) : uint4_t{0, 0, 0, 0};
+        for (int i = 0; i < NCT; ++i) xr[i] = *(const uint4_t*)(xrow[i] + step * kKTile);
     };
     auto store_x = [&](int buf) {
         uint8_t* base = c.lds + buf * (c.mc * kLdsRow) + (tid >> 4) * kLdsRow + piece * 16;
@@ -161,6 +161,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             }
         };
         auto load_w = [&](int slot, int step) {
+            step = step < last ? step : last;
 #pragma unroll
             for (int t = 0; t < NA; ++t) raw[slot][t] = *(const uint4_t*)(wdata[t] + step * (kKTile / 2));
         };
@@ -191,20 +192,20 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         load_x(0);
         load_sz(sz_cur, 0);
         load_w(0, 0);
-        if (1 < n_steps) load_w(1, 1);
-        if (2 < n_steps) load_w(2, 2);
+        load_w(1, 1);
+        load_w(2, 2);
         store_x(0);
-        if (1 < n_steps) load_x(1);
+        load_x(1);
         __syncthreads();
         for (int S = 0; 4 * S < n_steps; ++S) {
-            if (4 * (S + 1) < n_steps) load_sz(sz_next, S + 1);
+            load_sz(sz_next, S + 1);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int step = 4 * S + j;
                 if (step < n_steps) {
-                    if (step + 1 < n_steps) store_x((j + 1) & 1);
-                    if (step + 2 < n_steps) load_x(step + 2);
-                    if (step + 3 < n_steps) load_w((j + 3) & 3, step + 3);
+                    store_x((j + 1) & 1);          // past the last step this writes a tile nobody reads
+                    load_x(step + 2);
+                    load_w((j + 3) & 3, step + 3);
                     compute(j, j & 1, j);
                     __syncthreads();
                 }
@@ -214,7 +215,9 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         }
     } else {
         uint4_t wf[4][NA];
+        const int last_sub = n_steps * 4 - 1;
         auto load_w = [&](int slot, int sub) {   // sub = sub-step index over the whole contraction range (32 columns each)
+            sub = sub < last_sub ? sub : last_sub;
 #pragma unroll
             for (int t = 0; t < NA; ++t) wf[slot][t] = *(const uint4_t*)(wdata[t] + sub * 64);
         };
@@ -227,21 +230,19 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                 for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, wf[slot][t]), b, acc[t][j2]);
             }
         };
-        const int n_sub = n_steps * 4;
         load_x(0);
         load_w(0, 0);
         load_w(1, 1);
         load_w(2, 2);
         store_x(0);
-        if (1 < n_steps) load_x(1);
+        load_x(1);
         __syncthreads();
         for (int step = 0; step < n_steps; ++step) {
-            if (step + 1 < n_steps) store_x((step + 1) & 1);
-            if (step + 2 < n_steps) load_x(step + 2);
+            store_x((step + 1) & 1);               // past the last step this writes a tile nobody reads
+            load_x(step + 2);
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int sub = step * 4 + s;
-                if (sub + 3 < n_sub) load_w((s + 3) & 3, sub + 3);
+                load_w((s + 3) & 3, step * 4 + s + 3);
                 compute_sub(s, step & 1, s);
             }
             __syncthreads();
