@@ -297,6 +297,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-tokens", type=int, default=-1, help="oracle sample size (0 = skip, -1 = default)")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run a plain device-to-device copy of this many MiB three times: the known-size kernel "
+                         "that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -314,6 +317,14 @@ def main() -> int:
         res = run_chain_workload(args, wl, mm, workload, torch, np)
     else:
         res = run_layer_workload(args, wl, mm, workload, torch, np)
+
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "MoE-layer tokens/s + effective weight HBM GB/s (% of peak), Mixtral shape",

@@ -162,8 +162,6 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
         half_t* hs = h + (size_t)s * f;
         if (int4) {
             ActI4 act[NCH];
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) load_act_i4(x + c * 2048 + lane * 32, act[c]);
             constexpr int gpr = d / 64;
             constexpr int RB = kUpRowsI4;
             const uint32_t lane_q = lane * 16, lane_g = (lane >> 1) * 2;   // byte offsets inside a row
@@ -211,8 +209,12 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                 if (lane < RB && r + lane < r1) hs[r + lane] = (half_t)silu_mul(am, bm);
             };
             // two register buffers: the loads of the next rows are in flight while the current ones are used
+            // the first weight rows are requested before the token: they come from HBM, the token from L2
             Rows A, B;
             load_rows(A, r0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) load_act_i4(x + c * 2048 + lane * 32, act[c]);
             for (int r = r0; r < r1; r += 2 * RB) {
                 if (r + RB < r1) load_rows(B, r + RB);
                 __builtin_amdgcn_sched_barrier(0);
@@ -228,8 +230,6 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
         } else {
             constexpr int NL = d / 512;   // 128-bit loads per row
             ActF16 act[NL];
-#pragma unroll
-            for (int c = 0; c < NL; ++c) load_act_f16(x + c * 512 + lane * 8, act[c]);
             const uint8_t* w1 = ee.w1.data;
             const uint8_t* w3 = ee.w3.data;
             const uint32_t lane_w = lane * 16;
@@ -253,6 +253,9 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
             };
             Row A, B;
             load_row(A, w1, r0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < NL; ++c) load_act_f16(x + c * 512 + lane * 8, act[c]);
             for (int r = r0; r < r1; ++r) {
                 load_row(B, w3, r);
                 __builtin_amdgcn_sched_barrier(0);
