@@ -86,7 +86,8 @@ bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L
 MfmaPlan plan_for(const moe_layer* L, int rows) {
     MfmaPlan p = plan_mfma(rows, L->d_model, L->d_ff, L->n_experts);
     if (tuning().mfma_ct) p.ct = tuning().mfma_ct;
-    if (tuning().mfma_splits && (L->d_ff / 128) % tuning().mfma_splits == 0) p.down_splits = tuning().mfma_splits;
+    if (tuning().mfma_splits && (L->d_ff / 128) % tuning().mfma_splits == 0 && (L->d_ff / 128) / tuning().mfma_splits >= 2)
+        p.down_splits = tuning().mfma_splits;
     return p;
 }
 

@@ -20,8 +20,16 @@ namespace moemix {
 
 namespace {
 
+#ifdef MOEMIX_NT_WEIGHTS
+#define MOEMIX_WLOAD(p) __builtin_nontemporal_load(p)
+#else
+#define MOEMIX_WLOAD(p) (*(p))
+#endif
+#ifndef MOEMIX_SPB_MAX
+#define MOEMIX_SPB_MAX 2
+#endif
+#define MOEMIX_SPB(ct) ((8 / (ct)) < MOEMIX_SPB_MAX ? (8 / (ct)) : MOEMIX_SPB_MAX)
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
-constexpr int kLdsRow = kKTile * 2 + 16;    // bytes per activation row in LDS: 16 bytes of padding spread the banks
 
 struct MfmaArgs {
     DevExperts ex;
@@ -37,19 +45,43 @@ struct MfmaArgs {
     int32_t* status;
 };
 
+// Pointers into device (global) memory, typed as such, and a pin that keeps a uniform pointer in scalar
+// registers so that "uniform base + 32-bit lane offset" compiles to the scalar-base addressing form.
+#define MOEMIX_GLOBAL __attribute__((address_space(1)))
+typedef const char MOEMIX_GLOBAL* gptr_t;
+__device__ __forceinline__ gptr_t scalar_ptr(const void* p) {
+    gptr_t g = (gptr_t)p;
+    asm volatile("" : "+s"(g));
+    return g;
+}
+
 __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
+// (a & mask) | bits in one instruction: the mask travels in a scalar register, the OR-ed bits in a vector one
+// (the instruction may read a single scalar operand, which is why the compiler does not form it by itself).
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits));
+    return r;
+}
+
+// fp16 pairs (1024, 1024) and (64, 64) held in vector registers (not volatile: identical copies are merged).
+__device__ __forceinline__ uint32_t vreg_const(uint32_t v) {
+    uint32_t m;
+    asm("v_mov_b32 %0, %1" : "=v"(m) : "s"(v));
+    return m;
+}
+
 // Eight 4-bit codes of one word -> their dequantized fp16 values, in the order (0,4,1,5,2,6,3,7).
-__device__ __forceinline__ half8_t expand_word(uint32_t w, half2_t s2, half2_t z2) {
-    const half2_t k1024 = {(half_t)1024.0f, (half_t)1024.0f}, k64 = {(half_t)64.0f, (half_t)64.0f};
+__device__ __forceinline__ half8_t expand_word(uint32_t w, half2_t s2, half2_t z2, uint32_t m1024, uint32_t m64) {
     const uint32_t w8 = w >> 8;
     // low nibbles land in the mantissa of 1024 (ulp 1), high nibbles in the mantissa of 64 (ulp 1/16, code << 4)
-    const half2_t q04 = as_half2((w & 0x000F000Fu) | 0x64006400u) - k1024;
-    const half2_t q15 = as_half2((w & 0x00F000F0u) | 0x54005400u) - k64;
-    const half2_t q26 = as_half2((w8 & 0x000F000Fu) | 0x64006400u) - k1024;
-    const half2_t q37 = as_half2((w8 & 0x00F000F0u) | 0x54005400u) - k64;
+    const half2_t q04 = as_half2(and_or(w, 0x000F000Fu, m1024)) - as_half2(m1024);
+    const half2_t q15 = as_half2(and_or(w, 0x00F000F0u, m64)) - as_half2(m64);
+    const half2_t q26 = as_half2(and_or(w8, 0x000F000Fu, m1024)) - as_half2(m1024);
+    const half2_t q37 = as_half2(and_or(w8, 0x00F000F0u, m64)) - as_half2(m64);
     const half2_t a = __builtin_elementwise_fma(q04, s2, z2), b = __builtin_elementwise_fma(q15, s2, z2);
     const half2_t c = __builtin_elementwise_fma(q26, s2, z2), d = __builtin_elementwise_fma(q37, s2, z2);
     return half8_t{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
@@ -70,45 +102,52 @@ struct TileCtx {
 
 // UP: two matrices (w1, w3), 2 tiles of 16 weight rows per wavefront (workgroup: 128 rows);
 // down: one matrix (w2), 4 tiles per wavefront (workgroup: 256 rows).  Either way 4 A operands per step.
-// NCT = 16-row activation tiles computed (a power of two >= the tiles that hold rows; the rest is zeros), so
-// the inner loops are straight-line code the compiler can software-pipeline.
-template <bool UP, bool INT4, int NCT>
+// NCT = 16-row activation tiles computed (a power of two >= the tiles that hold rows), so the inner loops are
+// straight-line code.  SPB = 128-column steps per LDS stage (and per barrier): a launch with few activation
+// rows per chunk stages more columns at a time, so that the LDS buffers always hold 128 x 128 elements.
+template <bool UP, bool INT4, int NCT, int SPB>
 __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
     constexpr int NA = 4;
+    constexpr int NT = UP ? 128 : 256;
+    constexpr int kStride = SPB * kKTile * 2 + 16;     // bytes per activation row of an LDS stage (16 bytes of padding)
+    constexpr int PPR = 16 * SPB;                      // 16-byte pieces per row of a stage
+    constexpr int RPP = 256 / PPR;                     // rows the 256 threads cover in one pass
+    constexpr int NP = NCT * SPB;                      // pieces per thread and stage
     const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, c4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = c.K, N = c.N, n_steps = c.n_steps;
-    constexpr int NT = UP ? 128 : 256;
+    const int last = n_steps - 1;    // loads that would run past the contraction range repeat the last step instead
+    const int buf_bytes = c.mc * kStride;
 
-    // ---- activation rows this thread stages: rows tid/16 + 16 i, 16-byte piece tid%16 of each 256-byte row slice.
+    // ---- activation pieces this thread stages: column piece tid % PPR of rows tid / PPR + RPP i.
     // Rows past the end of the chunk repeat its last row: their products are computed and never stored.
-    const int piece = tid & 15;
-    const half_t* xrow[NCT];
+    const int pcol = tid % PPR, pstep = pcol >> 4;     // pstep: which 128-column step of the stage the piece is in
+    const half_t* xrow[NP];
 #pragma unroll
-    for (int i = 0; i < NCT; ++i) {
-        int rr = (tid >> 4) + 16 * i;
+    for (int i = 0; i < NP; ++i) {
+        int rr = tid / PPR + RPP * i;
         rr = rr < c.rows ? rr : c.rows - 1;
         const int g = c.begin + c.m0 + rr;
         const size_t src = (UP && c.perm) ? (size_t)(c.perm[g] / c.top_k) : (size_t)g;
-        xrow[i] = c.in + src * K + c.k_begin + piece * 8;
+        xrow[i] = c.in + src * K + c.k_begin + (pcol & 15) * 8;
     }
-    const int last = n_steps - 1;    // loads that would run past the contraction range repeat the last step instead
-    uint4_t xr[NCT];
-    auto load_x = [&](int step) {
+    uint4_t xr[NP];
+    auto load_x = [&](int stage) {
+        int step = stage * SPB + pstep;
         step = step < last ? step : last;
 #pragma unroll
-        for (int i = 0; i < NCT; ++i) xr[i] = *(const uint4_t*)(xrow[i] + step * kKTile);
+        for (int i = 0; i < NP; ++i) xr[i] = *(const uint4_t*)(xrow[i] + step * kKTile);
     };
     auto store_x = [&](int buf) {
-        uint8_t* base = c.lds + buf * (c.mc * kLdsRow) + (tid >> 4) * kLdsRow + piece * 16;
+        uint8_t* base = c.lds + buf * buf_bytes + (tid / PPR) * kStride + pcol * 16;
 #pragma unroll
-        for (int i = 0; i < NCT; ++i) {
+        for (int i = 0; i < NP; ++i) {
             uint4_t v = xr[i];
             if (INT4) {   // element order (0,4,1,5,2,6,3,7) inside each group of 8, as expand_word delivers codes
                 const half8_t h = __builtin_bit_cast(half8_t, v);
                 v = __builtin_bit_cast(uint4_t, half8_t{h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]});
             }
-            *(uint4_t*)(base + i * 16 * kLdsRow) = v;
+            *(uint4_t*)(base + i * RPP * kStride) = v;
         }
     };
 
@@ -138,114 +177,164 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
         for (int j = 0; j < NCT; ++j) acc[t][j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // B operand of activation tile j, sub-step s: lane (r16, c4) reads 8 elements of activation row 16 j + r16
-    const int b_lane = r16 * kLdsRow + (INT4 ? c4 * 64 : c4 * 16);
-    constexpr int b_step = INT4 ? 16 : 64;
+    // B operand of activation tile j, step q of the stage, sub-step s: lane (r16, c4) reads 8 elements of
+    // activation row 16 j + r16
+    const int b_lane = r16 * kStride + (INT4 ? c4 * 64 : c4 * 16);
+    constexpr int b_sub = INT4 ? 16 : 64;
 
-    // Pipeline, per 128-column step: the activation tile of step+1 is written to the other LDS buffer at the
-    // top of the step (its loads were issued a step earlier), the loads of step+2 are issued, weights run three
-    // steps (4-bit) or three 32-column sub-steps (16-bit) ahead in a ring of four register buffers, and one
-    // barrier closes the step.
-    if (INT4) {
-        const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of the 128-column step
-        uint4_t raw[4][NA];
-        uint32_t sz_cur[NA][2], sz_next[NA][2];
-        // scales and zeros of four steps with one load: lane (r16, c4) fetches the pair of groups of step 4 S + c4
-        auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
-            int step = 4 * S + c4;
-            step = step < n_steps ? step : n_steps - 1;
+    // Pipeline: at the first step of a stage the activation data of the next stage goes to the other LDS buffer
+    // (its loads were issued a stage earlier) and the loads of the stage after that are issued; weights run three
+    // steps (4-bit) or three 32-column sub-steps (16-bit) ahead in a ring of four register buffers; one barrier
+    // closes each stage.  Steps are processed in groups of G = max(4, SPB) so that ring slots, the quarter of the
+    // scale loads and the place of the barriers are compile-time constants.
+    constexpr int G = SPB > 4 ? SPB : 4;
+    uint4_t ring[4][NA];                 // 16-bit: one 32-column sub-step of weights per slot
+    uint32_t sz_cur[NA][2], sz_next[NA][2];
+    const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
+    const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
+    // scales and zeros of four steps with one load: lane (r16, c4) fetches the pair of groups of step 4 S + c4
+    auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
+        int step = 4 * S + c4;
+        step = step < last ? step : last;
 #pragma unroll
-            for (int t = 0; t < NA; ++t) {
-                dst[t][0] = *(const uint32_t*)(wscale[t] + step * 2);
-                dst[t][1] = *(const uint32_t*)(wzero[t] + step * 2);
-            }
-        };
-        auto load_w = [&](int slot, int step) {
-            step = step < last ? step : last;
-#pragma unroll
-            for (int t = 0; t < NA; ++t) raw[slot][t] = *(const uint4_t*)(wdata[t] + step * (kKTile / 2));
-        };
-        auto compute = [&](int slot, int xbuf, int j) {
-            const uint8_t* xb = c.lds + xbuf * (c.mc * kLdsRow) + b_lane;
-            half2_t s2[NA], z2[NA];
-            const int src = (r16 + 16 * j) * 4;     // the lane of this row that fetched step j of the four
-#pragma unroll
-            for (int t = 0; t < NA; ++t) {
-                const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][0]);
-                const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][1]);
-                s2[t] = as_half2(__builtin_amdgcn_perm(sd, sd, sel));
-                z2[t] = as_half2(__builtin_amdgcn_perm(zd, zd, sel));
-            }
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                half8_t af[NA];
-#pragma unroll
-                for (int t = 0; t < NA; ++t) af[t] = expand_word(raw[slot][t][s], s2[t], z2[t]);
-#pragma unroll
-                for (int j2 = 0; j2 < NCT; ++j2) {
-                    const half8_t b = *(const half8_t*)(xb + j2 * 16 * kLdsRow + s * b_step);
-#pragma unroll
-                    for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(af[t], b, acc[t][j2]);
-                }
-            }
-        };
-        load_x(0);
-        load_sz(sz_cur, 0);
-        load_w(0, 0);
-        load_w(1, 1);
-        load_w(2, 2);
-        store_x(0);
-        load_x(1);
-        __syncthreads();
-        for (int S = 0; 4 * S < n_steps; ++S) {
-            load_sz(sz_next, S + 1);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int step = 4 * S + j;
-                if (step < n_steps) {
-                    store_x((j + 1) & 1);          // past the last step this writes a tile nobody reads
-                    load_x(step + 2);
-                    load_w((j + 3) & 3, step + 3);
-                    compute(j, j & 1, j);
-                    __syncthreads();
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+        for (int t = 0; t < NA; ++t) {
+            dst[t][0] = *(const uint32_t*)(wscale[t] + step * 2);
+            dst[t][1] = *(const uint32_t*)(wzero[t] + step * 2);
         }
+    };
+    // 4-bit codes take a detour through LDS so that device memory is read in whole 128-byte lines: one load
+    // instruction fetches, for 8 weight rows, the 128 bytes (256 columns = two steps) of each row with 8 lanes
+    // per row; the pieces are written to a wavefront-private LDS region (16-byte slots XOR-swizzled by row so that
+    // neither side has bank conflicts) and read back in operand layout, lane (r16, c4) <- slot 4 * (step & 1) + c4.
+    uint4_t stg[NA][2];                  // staged loads of the next pair of steps
+    uint4_t apc[NA][2];                  // codes of the current pair of steps in operand layout
+    uint32_t goff[NA][2];                // per-lane byte offsets of the staged rows inside the code matrix
+    gptr_t cbase[NA];                    // uniform: start of the contraction range in the code matrix
+    uint8_t* const wreg = c.lds + 2 * buf_bytes + wave * (NA * 2048);
+    const int w_wr = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) * 16);
+    const int w_rd = r16 * 128;
+    const int last_pair = (n_steps + 1) / 2 - 1;
+    if (INT4) {
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            const int tile = UP ? (t >> 1) : t;
+            const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+            cbase[t] = scalar_ptr(m.data + (c.k_begin >> 1));
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                int row = c.n0 + wave * (NT / 4) + tile * 16 + 8 * hb + (lane >> 3);
+                row = row < N ? row : N - 1;
+                goff[t][hb] = (uint32_t)row * (uint32_t)(K >> 1) + (lane & 7) * 16;
+            }
+        }
+    }
+    auto load_pair = [&](int pair) {           // a pair past the end repeats the last one (never used)
+        pair = pair < last_pair ? pair : last_pair;
+        // an odd number of steps: the last pair's second half would leave the row only in the last row of the last
+        // split, so the pair is moved back by one step there (its second half is then never used)
+        const int byte0 = (2 * pair + 2 <= n_steps) ? pair * 128 : pair * 128 - 64;
+#pragma unroll
+        for (int t = 0; t < NA; ++t)
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) stg[t][hb] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0);
+    };
+    auto stage_to_lds = [&]() {
+#pragma unroll
+        for (int t = 0; t < NA; ++t)
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) *(uint4_t*)(wreg + t * 2048 + hb * 1024 + w_wr) = stg[t][hb];
+    };
+    auto lds_to_operands = [&](int pair) {
+        // (for the moved-back last pair of an odd range the wanted step sits in the second half)
+        const int shift = (2 * pair + 2 <= n_steps) ? 0 : 4;
+#pragma unroll
+        for (int t = 0; t < NA; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int slot = (4 * h + c4 + shift) & 7;
+                apc[t][h] = *(const uint4_t*)(wreg + t * 2048 + w_rd + ((slot ^ (r16 & 7)) * 16));
+            }
+    };
+    const int last_sub = n_steps * 4 - 1;
+    auto load_w16 = [&](int slot, int sub) {   // sub = sub-step index over the whole contraction range (32 columns each)
+        sub = sub < last_sub ? sub : last_sub;
+#pragma unroll
+        for (int t = 0; t < NA; ++t) ring[slot][t] = MOEMIX_WLOAD((const uint4_t*)(wdata[t] + sub * 64));
+    };
+
+    load_x(0);
+    if (INT4) {
+        load_sz(sz_cur, 0);
+        load_pair(0);
+        stage_to_lds();
+        load_pair(1);
     } else {
-        uint4_t wf[4][NA];
-        const int last_sub = n_steps * 4 - 1;
-        auto load_w = [&](int slot, int sub) {   // sub = sub-step index over the whole contraction range (32 columns each)
-            sub = sub < last_sub ? sub : last_sub;
+        load_w16(0, 0); load_w16(1, 1); load_w16(2, 2);
+    }
+    store_x(0);
+    load_x(1);
+    __syncthreads();
+
+    for (int base = 0; base < n_steps; base += G) {
 #pragma unroll
-            for (int t = 0; t < NA; ++t) wf[slot][t] = *(const uint4_t*)(wdata[t] + sub * 64);
-        };
-        auto compute_sub = [&](int slot, int xbuf, int s) {
-            const uint8_t* xb = c.lds + xbuf * (c.mc * kLdsRow) + b_lane;
+        for (int g = 0; g < G; ++g) {
+            const int step = base + g;
+            if (step < n_steps) {                                   // uniform; false only in the last group
+                const int stage = step / SPB;
+                const uint8_t* xb = c.lds + (stage & 1) * buf_bytes + b_lane + (g % SPB) * (kKTile * 2);
+                if (g % SPB == 0) {
+                    store_x((stage + 1) & 1);                       // past the last stage this writes data nobody reads
+                    load_x(stage + 2);
+                }
+                if (INT4) {
+                    if (g % 4 == 0) {
+                        if (step > 0) {
 #pragma unroll
-            for (int j2 = 0; j2 < NCT; ++j2) {
-                const half8_t b = *(const half8_t*)(xb + j2 * 16 * kLdsRow + s * b_step);
+                            for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+                        }
+                        load_sz(sz_next, step / 4 + 1);
+                    }
+                    if (g % 2 == 0) lds_to_operands(step >> 1);
+                    half2_t s2[NA], z2[NA];
+                    const int src = (r16 + 16 * (g & 3)) * 4;       // the lane of this row that fetched this step's scales
 #pragma unroll
-                for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, wf[slot][t]), b, acc[t][j2]);
+                    for (int t = 0; t < NA; ++t) {
+                        const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][0]);
+                        const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][1]);
+                        s2[t] = as_half2(__builtin_amdgcn_perm(sd, sd, sel));
+                        z2[t] = as_half2(__builtin_amdgcn_perm(zd, zd, sel));
+                    }
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        half8_t af[NA];
+#pragma unroll
+                        for (int t = 0; t < NA; ++t) af[t] = expand_word(apc[t][g & 1][sb], s2[t], z2[t], m1024, m64);
+#pragma unroll
+                        for (int j2 = 0; j2 < NCT; ++j2) {
+                            const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
+#pragma unroll
+                            for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(af[t], b, acc[t][j2]);
+                        }
+                    }
+                    if (g % 2 == 1 || step == last) {               // the pair is used up: the next one takes its place
+                        stage_to_lds();
+                        load_pair((step >> 1) + 2);
+                    }
+                } else {
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        load_w16((sb + 3) & 3, step * 4 + sb + 3);
+#pragma unroll
+                        for (int j2 = 0; j2 < NCT; ++j2) {
+                            const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
+#pragma unroll
+                            for (int t = 0; t < NA; ++t)
+                                acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, ring[sb][t]), b, acc[t][j2]);
+                        }
+                    }
+                }
+                if (g % SPB == SPB - 1 || step == last) __syncthreads();
             }
-        };
-        load_x(0);
-        load_w(0, 0);
-        load_w(1, 1);
-        load_w(2, 2);
-        store_x(0);
-        load_x(1);
-        __syncthreads();
-        for (int step = 0; step < n_steps; ++step) {
-            store_x((step + 1) & 1);               // past the last step this writes a tile nobody reads
-            load_x(step + 2);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                load_w((s + 3) & 3, step * 4 + s + 3);
-                compute_sub(s, step & 1, s);
-            }
-            __syncthreads();
         }
     }
 
@@ -283,7 +372,8 @@ template <bool UP, int CT>
 __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     constexpr int MC = 16 * CT;                  // activation rows per chunk
     constexpr int NT = UP ? 128 : 256;           // weight rows per workgroup
-    extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][kLdsRow]
+    constexpr int SPB = MOEMIX_SPB(CT);          // 128-column steps per LDS stage
+    extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][SPB * 256 + 16]
     const int tid = threadIdx.x;
 
     // ---- which expert, which rows
@@ -326,19 +416,19 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     const bool int4 = ee.prec == MOE_PREC_INT4G64;
     const int nct = (c.rows + 15) >> 4;          // 16-row tiles that hold any rows
     if (CT >= 8 && nct > 4) {
-        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT)>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT), SPB>(c, ee, out_base);
     } else if (CT >= 4 && nct > 2) {
-        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT)>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT), SPB>(c, ee, out_base);
     } else if (CT >= 2 && nct > 1) {
-        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT)>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT)>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT), SPB>(c, ee, out_base);
     } else {
-        if (int4) tile_body<UP, true, 1>(c, ee, out_base); else tile_body<UP, false, 1>(c, ee, out_base);
+        if (int4) tile_body<UP, true, 1, SPB>(c, ee, out_base); else tile_body<UP, false, 1, SPB>(c, ee, out_base);
     }
 }
 
 template <bool UP, int CT>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
-    const size_t lds_bytes = 2u * 16 * CT * kLdsRow;
+    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * 4 * 2048;   // + 4 wavefronts x 4 operands x 2 KB
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -368,7 +458,8 @@ int chunk_slots(const RowMap& rows, int P, int E, int ct) {
 
 }  // namespace
 
-bool mfma_shape_ok(int d, int f) { return d % kKTile == 0 && f % kKTile == 0; }
+// every contraction range must hold at least two 128-column steps (4-bit codes are fetched in pairs of steps)
+bool mfma_shape_ok(int d, int f) { return d % kKTile == 0 && f % kKTile == 0 && d >= 2 * kKTile && f >= 2 * kKTile; }
 
 MfmaPlan plan_mfma(int P, int d, int f, int E) {
     MfmaPlan p;
@@ -379,7 +470,7 @@ MfmaPlan plan_mfma(int P, int d, int f, int E) {
     const int base = ((d + 255) / 256) * (P / (16 * p.ct) + 1);
     int best = 1;
     for (int s = 1; s <= 16; ++s)
-        if (steps % s == 0 && base * s <= 1024) best = s;
+        if (steps % s == 0 && steps / s >= 2 && base * s <= 1024) best = s;
     p.down_splits = best;
     return p;
 }
