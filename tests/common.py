@@ -105,6 +105,11 @@ PREFILL = Config("prefill", 4096, 14336, 8, 2, 512, (2, 3, 4, 5, 6, 7), zipf=1.2
 # d and f are not multiples of the kernels' larger tiles, T*k/E is ragged.
 MEDIUM = Config("medium", 1024, 2816, 8, 2, 24, (1, 2, 5, 7))
 MEDIUM_ZIPF = Config("medium_zipf", 1024, 2816, 8, 2, 96, (2, 3, 4, 5, 6, 7), zipf=1.2)
+# Shapes that stress the matrix-core path: odd numbers of 128-column steps in both contractions (d = 5 x 128,
+# f = 7 x 128) and a ragged last tile of 256 weight rows in the down-projection (640 = 2 x 256 + 128).
+ODD_STEPS = Config("odd_steps", 640, 896, 8, 2, 40, (0, 3, 4, 6))
+# d and f multiples of 64 but not of 128: served by the shape-agnostic kernels.
+GENERIC = Config("generic", 192, 320, 4, 2, 9, (1, 2))
 # Smallest shape the batch-1 decode kernels take (d and f multiples of 2048), with a precision mix.
 DECODE_SMALL = Config("decode_small", 2048, 4096, 8, 2, 1, (1, 2, 5, 7))
 

@@ -9,7 +9,7 @@ torch = pytest.importorskip("torch")
 from paper_2407_14417_amd import binding as mm
 from paper_2407_14417_amd import synth
 from tests import common
-from tests.common import TINY, MEDIUM, MEDIUM_ZIPF, build_workload, assert_ffn_close
+from tests.common import TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, build_workload, assert_ffn_close
 from tests.gpu_common import dev, device_layer, device_mat
 
 pytestmark = pytest.mark.gpu
@@ -186,6 +186,37 @@ def test_expert_ffn_both_precisions(orc, cfg, n):
         assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n={n} e={e}")
 
 
+@pytest.mark.parametrize("n", [2, 16, 17, 33, 130, 300])
+def test_expert_ffn_odd_steps_ragged_tiles_many_chunks(orc, n):
+    """Matrix-core path: odd step counts (the last pair of 4-bit steps is fetched one step back), a ragged tile of
+    weight rows, row counts from one partial 16-row tile to three 128-row chunks."""
+    cfg = ODD_STEPS
+    wl = build_workload(cfg, orc, experts_needed=(0, 1))
+    assert wl.experts[0].int4 and not wl.experts[1].int4
+    layer = device_layer(wl)
+    x = synth.normal_f16((n, cfg.d), 1.0, 37, synth.x_stream(0))
+    ws = mm.alloc_workspace(layer, (n + cfg.k - 1) // cfg.k)
+    for e in (0, 1):
+        _say(f"expert_ffn cfg={cfg.name} n={n} expert={e}")
+        y = torch.full((n, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+        mm.moe_expert_ffn_mixed(layer, e, dev(x), y, ws)
+        assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n={n} e={e}")
+
+
+@pytest.mark.parametrize("n", [1, 4, 9])
+def test_expert_ffn_shape_agnostic_kernels(orc, n):
+    cfg = GENERIC
+    wl = build_workload(cfg, orc, experts_needed=(0, 1))
+    layer = device_layer(wl)
+    x = synth.normal_f16((n, cfg.d), 1.0, 41, synth.x_stream(0))
+    ws = mm.alloc_workspace(layer, (n + cfg.k - 1) // cfg.k)
+    for e in (0, 1):
+        _say(f"expert_ffn cfg={cfg.name} n={n} expert={e}")
+        y = torch.empty((n, cfg.d), dtype=torch.float32, device="cuda")
+        mm.moe_expert_ffn_mixed(layer, e, dev(x), y, ws)
+        assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n={n} e={e}")
+
+
 def test_expert_ffn_identity_weights_exact_structure(orc):
     """One-entry matrices: catches a transposed operand or swapped w1/w3 in the kernels."""
     d, f = 128, 192
@@ -218,12 +249,29 @@ def _run_layer(layer, x_np, cfg):
     return out.cpu().numpy(), idx.cpu().numpy(), gate.cpu().numpy(), mm.moe_read_status(ws)
 
 
-@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC], ids=lambda c: c.name)
 def test_layer_forward(orc, cfg):
     wl = build_workload(cfg, orc)
     _say(f"layer_forward cfg={cfg.name}")
     out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
     ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    assert status == 0
+    assert np.array_equal(idx, ref_idx)
+    assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
+    assert_ffn_close(out, ref, cfg.name)
+
+
+def test_layer_forward_many_tokens_several_chunks_per_expert(orc):
+    """600 tokens with skewed routing: the busiest experts span several 128-row chunks of the matrix-core path,
+    the rarest fit in one partial tile; grouped rows come through the permutation."""
+    cfg = common.Config("medium_many", 1024, 2816, 8, 2, 600, (1, 2, 5, 7), zipf=1.2)
+    wl = build_workload(cfg, orc)
+    _say(f"layer_forward cfg={cfg.name}")
+    out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
+    ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    counts = np.bincount(ref_idx.reshape(-1), minlength=cfg.E)
+    _say(f"rows per expert: {counts.tolist()}")
+    assert counts.max() > 256 and counts.min() < 64
     assert status == 0
     assert np.array_equal(idx, ref_idx)
     assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
