@@ -54,6 +54,20 @@ WORKLOADS = {
 }
 
 
+def traffic_ratio(profile_name: str, key: str):
+    """HBM bytes fetched per launch over algorithmic bytes per launch, as measured with rocprofv3 --pmc FETCH_SIZE
+    (scaled by the same counter's reading for a plain copy of known size) and recorded in profiles/<name>:
+    a line `TRAFFIC_OVER_ALGORITHMIC <key> = <ratio>`.  None if no such record exists."""
+    f = ROOT / "profiles" / profile_name
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        parts = line.split()
+        if len(parts) == 4 and parts[0] == "TRAFFIC_OVER_ALGORITHMIC" and parts[1] == key and parts[2] == "=":
+            return float(parts[3])
+    return None
+
+
 class HipEvents:
     """hipEvent_t pairs through the HIP runtime that torch has already loaded."""
 
@@ -216,6 +230,12 @@ def run_layer_workload(args, wl, mm, workload, torch, np):
                 "frac": up_TFLOPs / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                 "avg_launch_us": float(up_ms.mean() * 1e3), "GBps": up_GBps,
                 "frac_of_hbm_peak_on_bytes": up_GBps / HBM_PEAK_GBPS}
+    ratio = traffic_ratio({"decode": "decode_b1_hbm_traffic.md"}.get(args.workload, "none"), "up_projection")
+    if ratio is not None:
+        roof["traffic"] = ratio * float(up_bytes.mean())          # bytes per launch, like `achieved`
+        roof["traffic_source"] = "profiles/decode_b1_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE, copy-calibrated): " \
+                                 f"fetched/algorithmic = {ratio}"
+    roof["algorithmic_bytes_per_launch"] = float(up_bytes.mean())
     roof.update(extra)
     roof["other_kernels"] = other
     return {
@@ -343,7 +363,7 @@ def main() -> int:
     result.update(res)
     cpu_tokens = args.cpu_tokens
     if cpu_tokens < 0:
-        cpu_tokens = {"decode": 8, "batched": 16, "prefill": 32, "chain": 0}[args.workload]
+        cpu_tokens = {"decode": 48, "batched": 48, "prefill": 64, "chain": 0}[args.workload]
     if cpu_tokens > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.seed, cpu_tokens)
     print(json.dumps(result))

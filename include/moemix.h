@@ -181,9 +181,45 @@ int moe_read_status(void* ws, moe_stream_t stream, int* status_bits);
  * hipEventRecord(start_event) / hipEventRecord(stop_event) on the stream it is launched on (one shot;
  * arm again for the next launch).  Events are hipEvent_t created by the caller with timing enabled.
  */
-enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_PERMUTE = 1, MOE_KERNEL_UP = 2, MOE_KERNEL_DOWN = 3, MOE_KERNEL_COMBINE = 4,
-       MOE_KERNEL_RMSNORM = 5 };
+enum { MOE_KERNEL_ROUTE = 0,   /* gating (with the RMSNorm of the chained configuration) */
+       MOE_KERNEL_PERMUTE = 1, /* grouping */
+       MOE_KERNEL_UP = 2,      /* up-projection + SiLU gate */
+       MOE_KERNEL_DOWN = 3,    /* down-projection (with the weighted average at one token) */
+       MOE_KERNEL_COMBINE = 4  /* weighted average of a multi-token call */ };
 int moe_trace_kernel(int kernel, void* start_event, void* stop_event);
+
+/*
+ * Partitioner / planner (§3, Eq. 1): host-only arithmetic, no device work.  From the GPU memory available and the
+ * task's preference it fills the expert table's two attributes for all `num_experts` experts of a model:
+ *   throughput preference: the number of 16-bit experts is Eq. 1,
+ *       Num_E,16 = floor((mem_gpu - size_non_expert - num_experts * size_e4) / (3 * size_e4))
+ *                  if mem_gpu > size_non_expert + num_experts * size_e4, else 0     (clamped to num_experts);
+ *   quality preference: `num_e4` experts are 4-bit, as the task asks.
+ * Which experts are 4-bit is a seeded random choice (§3: the quantized attribute is assigned at random).  The
+ * location attribute is then given out while the budget mem_gpu - size_non_expert - swap_bytes lasts, 4-bit
+ * experts first, then 16-bit ones, each class in expert order (§3: 4-bit experts go to the GPU first, a swap
+ * space is kept for expert misses).
+ * quantized, resident: HOST arrays of num_experts bytes (1 = 4-bit / 1 = in device memory), written by the call.
+ * Returns MOE_EINVAL on NULL arguments, size_e4 == 0, num_experts < 1 or num_e4 outside [0, num_experts].
+ */
+typedef enum { MOE_PREFER_THROUGHPUT = 0, MOE_PREFER_QUALITY = 1 } moe_preference;
+typedef struct {
+    uint64_t mem_gpu;         /* bytes of device memory the job may use */
+    uint64_t size_non_expert; /* bytes of the non-expert layers, always 16-bit and resident */
+    uint64_t size_e16;        /* bytes of one expert in 16-bit form */
+    uint64_t size_e4;         /* bytes of one expert in 4-bit form */
+    uint64_t swap_bytes;      /* device memory set aside for expert misses */
+    uint64_t seed;            /* of the random choice of 4-bit experts */
+    int32_t num_experts;      /* all experts of the model (layers x experts per layer) */
+    int32_t preference;       /* moe_preference */
+    int32_t num_e4;           /* quality preference only: requested number of 4-bit experts */
+} moe_plan_request;
+typedef struct {
+    int32_t num_e16, num_e4;           /* experts per precision */
+    int32_t resident_e16, resident_e4; /* of those, in device memory */
+    uint64_t bytes_resident;           /* size_non_expert + resident experts */
+} moe_plan_result;
+int moe_plan(const moe_plan_request* req, moe_plan_result* res, uint8_t* quantized, uint8_t* resident);
 
 /* Host string describing the last error returned on this thread ("" if none). */
 const char* moe_last_error(void);

@@ -23,7 +23,7 @@ STATUS_NOT_RESIDENT = 1 << 3
 EXPORTS = (
     "moe_workspace_bytes", "moe_route", "moe_permute", "moe_expert_ffn_mixed", "moe_layer_forward",
     "moe_chain_forward", "moe_dequant_int4", "moe_quantize_int4", "moe_synth_fill_f16", "moe_read_status",
-    "moe_last_error", "moe_version", "moe_trace_kernel",
+    "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan",
 )
 
 
@@ -46,6 +46,19 @@ class CLayer(ctypes.Structure):
                 ("top_k", ctypes.c_int32), ("w_gate", ctypes.c_void_p), ("gate_bias", ctypes.c_void_p),
                 ("experts", ctypes.POINTER(CExpert))]
 
+
+class CPlanRequest(ctypes.Structure):
+    _fields_ = [("mem_gpu", ctypes.c_uint64), ("size_non_expert", ctypes.c_uint64), ("size_e16", ctypes.c_uint64),
+                ("size_e4", ctypes.c_uint64), ("swap_bytes", ctypes.c_uint64), ("seed", ctypes.c_uint64),
+                ("num_experts", ctypes.c_int32), ("preference", ctypes.c_int32), ("num_e4", ctypes.c_int32)]
+
+
+class CPlanResult(ctypes.Structure):
+    _fields_ = [("num_e16", ctypes.c_int32), ("num_e4", ctypes.c_int32), ("resident_e16", ctypes.c_int32),
+                ("resident_e4", ctypes.c_int32), ("bytes_resident", ctypes.c_uint64)]
+
+
+PREFER_THROUGHPUT, PREFER_QUALITY = 0, 1
 
 _lib = None
 
@@ -74,6 +87,7 @@ def lib():
         L.moe_synth_fill_f16.argtypes = [vp, sz, sz, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_float, i32, vp]
         L.moe_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int)]
         L.moe_trace_kernel.argtypes = [i32, vp, vp]
+        L.moe_plan.argtypes = [ctypes.POINTER(CPlanRequest), ctypes.POINTER(CPlanResult), vp, vp]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_version.restype = i32
         for name in EXPORTS:
@@ -211,11 +225,24 @@ def moe_read_status(ws) -> int:
     return v.value
 
 
-KERNEL_ROUTE, KERNEL_PERMUTE, KERNEL_UP, KERNEL_DOWN, KERNEL_COMBINE, KERNEL_RMSNORM = range(6)
+KERNEL_ROUTE, KERNEL_PERMUTE, KERNEL_UP, KERNEL_DOWN, KERNEL_COMBINE = range(5)
 
 
 def moe_trace_kernel(kernel: int, start_event: int, stop_event: int) -> None:
     _check(lib().moe_trace_kernel(kernel, start_event, stop_event))
+
+
+def moe_plan(mem_gpu: int, size_non_expert: int, size_e16: int, size_e4: int, num_experts: int, preference: int,
+             num_e4: int = 0, seed: int = 0, swap_bytes: int = 0):
+    """Returns (CPlanResult, quantized list, resident list); host-only."""
+    req = CPlanRequest(mem_gpu, size_non_expert, size_e16, size_e4, swap_bytes, seed, num_experts, preference, num_e4)
+    res = CPlanResult()
+    q = (ctypes.c_uint8 * max(num_experts, 1))()
+    r = (ctypes.c_uint8 * max(num_experts, 1))()
+    rc = lib().moe_plan(ctypes.byref(req), ctypes.byref(res), q, r)
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_plan rejected the request")
+    return res, list(q)[:num_experts], list(r)[:num_experts]
 
 
 def moe_version() -> int:

@@ -123,12 +123,15 @@ int check_ws(const moe_layer* L, int T, void* ws, size_t ws_bytes, Workspace* ou
     return MOE_OK;
 }
 
-// gating -> grouping -> experts -> weighted average, all on `st`; x may alias nothing in ws except ws.xn.
-int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int T, const half_t* residual,
-               half_t* out, int32_t* idx_out, float* gate_out, const Workspace& w, bool reset_status, hipStream_t st) {
+// (RMSNorm +) gating -> grouping -> experts -> weighted average (+ residual), all on `st`.
+// rms_gain != null: the block input is RMSNorm(x) * rms_gain, computed by the gating kernel into ws.xn.
+int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int T, const half_t* rms_gain, float eps,
+               const half_t* residual, half_t* out, int32_t* idx_out, float* gate_out, const Workspace& w,
+               bool reset_status, hipStream_t st) {
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
     launch_route(x, (const half_t*)L->w_gate, L->gate_bias, T, d, E, k, w.idx, w.gate, idx_out, gate_out,
-                 reset_status ? w.status : nullptr, st);
+                 reset_status ? w.status : nullptr, st, rms_gain, eps, w.xn);
+    if (rms_gain) x = w.xn;
     if (T == 1 && decode_shape_ok(d, f)) {
         // batch-1 decode: no grouping needed, the weighted average is fused into the down-projection
         launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, tuning().up_blocks, st);
@@ -160,7 +163,7 @@ struct Trace {
     bool armed = false;
     hipEvent_t start = nullptr, stop = nullptr;
 };
-thread_local Trace g_trace[kKernelRmsnorm + 1];   // one slot per kernel id: several kernels of one call can be armed
+thread_local Trace g_trace[kKernelCount];   // one slot per kernel id: several kernels of one call can be armed
 }  // namespace
 
 void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop) { g_trace[kernel] = Trace{true, start, stop}; }
@@ -181,7 +184,7 @@ TraceScope::~TraceScope() {
 extern "C" {
 
 int moe_trace_kernel(int kernel, void* start_event, void* stop_event) {
-    if (kernel < 0 || kernel > kKernelRmsnorm || !start_event || !stop_event)
+    if (kernel < 0 || kernel >= kKernelCount || !start_event || !stop_event)
         return fail(MOE_EINVAL, "moe_trace_kernel: bad kernel id or NULL event");
     trace_arm(kernel, (hipEvent_t)start_event, (hipEvent_t)stop_event);
     return MOE_OK;
@@ -250,7 +253,7 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
     Workspace w;
     if (int rc = check_ws(layer, T, ws, ws_bytes, &w)) return rc;
     const DevExperts table = device_table(layer);
-    return layer_body(layer, table, (const half_t*)x, T, nullptr, (half_t*)out, topk_idx_out, topk_gate_out, w, true,
+    return layer_body(layer, table, (const half_t*)x, T, nullptr, 0.0f, nullptr, (half_t*)out, topk_idx_out, topk_gate_out, w, true,
                       (hipStream_t)stream);
 }
 
@@ -268,12 +271,12 @@ int moe_chain_forward(const moe_layer* layers, const void* const* rms_gain, int 
     Workspace w;
     if (int rc = check_ws(&layers[0], T, ws, ws_bytes, &w)) return rc;
     hipStream_t st = (hipStream_t)stream;
-    const int d = layers[0].d_model, k = layers[0].top_k;
+    const int k = layers[0].top_k;
     for (int l = 0; l < n_layers; ++l) {
         const DevExperts table = device_table(&layers[l]);
-        launch_rmsnorm((const half_t*)h, (const half_t*)rms_gain[l], T, d, eps, w.xn, st);
         int32_t* idx_out = topk_idx_out ? topk_idx_out + (size_t)l * T * k : nullptr;
-        if (int rc = layer_body(&layers[l], table, w.xn, T, (const half_t*)h, (half_t*)h, idx_out, nullptr, w, l == 0, st))
+        if (int rc = layer_body(&layers[l], table, (const half_t*)h, T, (const half_t*)rms_gain[l], eps, (const half_t*)h,
+                                (half_t*)h, idx_out, nullptr, w, l == 0, st))
             return rc;
     }
     return MOE_OK;

@@ -1,6 +1,6 @@
 // 16-bit glue around the expert kernels: weighted average of the selected experts' outputs
-// (paper §1), RMSNorm and residual add of the chained configuration (§3: non-expert parts are
-// always 16-bit).
+// (paper §1) with the residual add of the chained configuration (§3: non-expert parts are
+// always 16-bit).  The RMSNorm of that configuration lives in the gating kernel.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -54,38 +54,6 @@ void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, h
     const size_t n4 = n / 4;
     const int blocks = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
     reduce_splits_kernel<<<blocks, 256, 0, st>>>(y, splits, split_stride, n4);
-}
-
-// out[t, :] = fp16( h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * g ), one workgroup per token.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const half_t* __restrict__ h, const half_t* __restrict__ g, int d,
-                                                       float eps, half_t* __restrict__ out) {
-    __shared__ float part[4];
-    const int t = blockIdx.x, tid = threadIdx.x;
-    const half_t* hr = h + (size_t)t * d;
-    float ss = 0.0f;
-    for (int c = tid * 8; c < d; c += 256 * 8) {
-        const half8_t v = *(const half8_t*)(hr + c);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ss += (float)v[j] * (float)v[j];
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) part[tid >> 6] = ss;
-    __syncthreads();
-    const float total = (part[0] + part[1]) + (part[2] + part[3]);
-    const float inv = 1.0f / sqrtf(total / (float)d + eps);
-    for (int c = tid * 8; c < d; c += 256 * 8) {
-        const half8_t v = *(const half8_t*)(hr + c);
-        const half8_t gv = *(const half8_t*)(g + c);
-        half8_t o;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (half_t)((float)v[j] * inv * (float)gv[j]);
-        *(half8_t*)(out + (size_t)t * d + c) = o;
-    }
-}
-
-void launch_rmsnorm(const half_t* h, const half_t* g, int T, int d, float eps, half_t* out, hipStream_t st) {
-    TraceScope trace(kKernelRmsnorm, st);
-    rmsnorm_kernel<<<T, 256, 0, st>>>(h, g, d, eps, out);
 }
 
 // Fill kernel used instead of a memset node so that every launch sequence stays graph-capturable.

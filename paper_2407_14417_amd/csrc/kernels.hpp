@@ -17,8 +17,10 @@ struct RowMap {
     int direct_n;
 };
 
+// rms_gain != null: the gating input is RMSNorm(x) * rms_gain (fp16), which is also written to xn [T, d].
 void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, int d, int E, int k, int32_t* idx,
-                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st);
+                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st,
+                  const half_t* rms_gain = nullptr, float eps = 0.0f, half_t* xn = nullptr);
 void launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
                     int32_t* status, hipStream_t st);
 
@@ -57,7 +59,6 @@ void launch_combine(const float* y, int splits, size_t split_stride, const float
 // y[r, :] = sum_p y[p][r, :] for r < n (in place, into the first partial)
 void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, hipStream_t st);
 void launch_zero_words(int32_t* p, int n, hipStream_t st);
-void launch_rmsnorm(const half_t* h, const half_t* g, int T, int d, float eps, half_t* out, hipStream_t st);
 
 void launch_dequant_int4(const DevMat& m, int out, int in, half_t* w, hipStream_t st);
 void launch_quantize_int4(const half_t* w, int out, int in, uint8_t* packed, half_t* scale, half_t* zero,
@@ -71,7 +72,7 @@ namespace moemix {
 
 // Kernel ids for moe_trace_kernel (same values as MOE_KERNEL_* in the public header).
 enum KernelId { kKernelRoute = 0, kKernelPermute = 1, kKernelUp = 2, kKernelDown = 3, kKernelCombine = 4,
-                kKernelRmsnorm = 5 };
+                kKernelCount = 5 };
 
 // One-shot event bracket around the next launch of a given kernel on this thread.
 void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop);

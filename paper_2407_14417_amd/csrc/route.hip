@@ -15,18 +15,46 @@ __global__ __launch_bounds__(512) void route_kernel(const half_t* __restrict__ x
                                                      const float* __restrict__ bias, int d, int E, int k,
                                                      int32_t* __restrict__ idx, float* __restrict__ gate,
                                                      int32_t* __restrict__ idx2, float* __restrict__ gate2,
-                                                     int32_t* __restrict__ status) {
+                                                     int32_t* __restrict__ status, const half_t* __restrict__ rms_gain,
+                                                     float eps, half_t* __restrict__ xn) {
     __shared__ float part[8][EMAX];
     __shared__ float logit[EMAX];
+    __shared__ float sq[8];
     const int t = blockIdx.x;
     const int tid = threadIdx.x, n_waves = blockDim.x >> 6;
+    const int wave = tid >> 6, lane = tid & 63;
     if (t == 0 && tid == 0 && status) *status = 0;   // status word describes the call that starts here
     float acc[EMAX];
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) acc[e] = 0.0f;
     const half_t* xr = x + (size_t)t * d;
+    // chained configuration: the block input is RMSNorm(x) * gain, rounded to fp16; it is written to xn for the
+    // expert kernels and used for the logits in the same pass
+    float inv = 1.0f;
+    if (rms_gain) {
+        float ss = 0.0f;
+        for (int c = tid * 8; c < d; c += blockDim.x * 8) {
+            const half8_t v = *(const half8_t*)(xr + c);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss += (float)v[j] * (float)v[j];
+        }
+        ss = wave_total(ss);
+        if (lane == 0) sq[wave] = ss;
+        __syncthreads();
+        float total = 0.0f;
+        for (int w = 0; w < n_waves; ++w) total += sq[w];
+        inv = 1.0f / sqrtf(total / (float)d + eps);
+    }
     for (int c = tid * 8; c < d; c += blockDim.x * 8) {
-        const uint4_t xv = *(const uint4_t*)(xr + c);
+        uint4_t xv = *(const uint4_t*)(xr + c);
+        if (rms_gain) {
+            const half8_t v = __builtin_bit_cast(half8_t, xv), g = *(const half8_t*)(rms_gain + c);
+            half8_t o;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = (half_t)((float)v[j] * inv * (float)g[j]);
+            *(half8_t*)(xn + (size_t)t * d + c) = o;
+            xv = __builtin_bit_cast(uint4_t, o);
+        }
         uint4_t wv[EMAX];
 #pragma unroll
         for (int e = 0; e < EMAX; ++e)
@@ -40,7 +68,6 @@ __global__ __launch_bounds__(512) void route_kernel(const half_t* __restrict__ x
             }
         }
     }
-    const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) {
         if (e < E) {
@@ -85,14 +112,16 @@ __global__ __launch_bounds__(512) void route_kernel(const half_t* __restrict__ x
 }
 
 void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, int d, int E, int k, int32_t* idx,
-                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st) {
+                  float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st, const half_t* rms_gain,
+                  float eps, half_t* xn) {
     TraceScope trace(kKernelRoute, st);
     int threads = (d / 8 + 63) / 64 * 64;      // one 8-column chunk per thread when the row fits
     threads = threads < 64 ? 64 : (threads > 512 ? 512 : threads);
     if (E <= 8)
-        route_kernel<8><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+        route_kernel<8><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps, xn);
     else
-        route_kernel<MOE_MAX_EXPERTS><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status);
+        route_kernel<MOE_MAX_EXPERTS><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps,
+                                                               xn);
 }
 
 // One workgroup.  Wave w owns experts w, w+16: it walks all pairs in order, 64 at a time, and a
