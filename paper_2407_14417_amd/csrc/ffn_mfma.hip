@@ -25,6 +25,9 @@ namespace {
 #else
 #define MOEMIX_WLOAD(p) (*(p))
 #endif
+#ifndef MOEMIX_NA_SMALL
+#define MOEMIX_NA_SMALL 2
+#endif
 #ifndef MOEMIX_SPB_MAX
 #define MOEMIX_SPB_MAX 2
 #endif
@@ -100,15 +103,17 @@ struct TileCtx {
     uint8_t* lds;
 };
 
-// UP: two matrices (w1, w3), 2 tiles of 16 weight rows per wavefront (workgroup: 128 rows);
-// down: one matrix (w2), 4 tiles per wavefront (workgroup: 256 rows).  Either way 4 A operands per step.
+// A wavefront holds NA A operands (16-row tiles of weights) per step.  UP: two matrices (w1, w3), NA/2 tiles each
+// (workgroup of 4 wavefronts: 32 NA rows); down: one matrix (w2), NA tiles (workgroup: 64 NA rows).  NA = 4 for
+// chunks of many activation rows (each B operand read from LDS feeds 4 products), NA = 2 when a chunk holds at
+// most 32 rows: the kernel is then bound by the expansion of the codes, and half the registers per wavefront
+// buy twice the wavefronts per SIMD to hide its latencies.
 // NCT = 16-row activation tiles computed (a power of two >= the tiles that hold rows), so the inner loops are
 // straight-line code.  SPB = 128-column steps per LDS stage (and per barrier): a launch with few activation
 // rows per chunk stages more columns at a time, so that the LDS buffers always hold 128 x 128 elements.
-template <bool UP, bool INT4, int NCT, int SPB>
+template <bool UP, bool INT4, int NCT, int SPB, int NA>
 __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
-    constexpr int NA = 4;
-    constexpr int NT = UP ? 128 : 256;
+    constexpr int NT = UP ? 32 * NA : 64 * NA;     // weight rows per workgroup: 16 NA / (matrices) per wavefront
     constexpr int kStride = SPB * kKTile * 2 + 16;     // bytes per activation row of an LDS stage (16 bytes of padding)
     constexpr int PPR = 16 * SPB;                      // 16-byte pieces per row of a stage
     constexpr int RPP = 256 / PPR;                     // rows the 256 threads cover in one pass
@@ -347,8 +352,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             if (UP) {
                 half_t* h = (half_t*)out_base + g * N;
 #pragma unroll
-                for (int tile = 0; tile < 2; ++tile) {
-                    const int col = c.n0 + wave * 32 + tile * 16 + c4 * 4;
+                for (int tile = 0; tile < NA / 2; ++tile) {
+                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
                     if (col < N) {
                         half4_t o;
 #pragma unroll
@@ -359,8 +364,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             } else {
                 float* y = (float*)out_base + g * N;
 #pragma unroll
-                for (int tile = 0; tile < 4; ++tile) {
-                    const int col = c.n0 + wave * 64 + tile * 16 + c4 * 4;
+                for (int tile = 0; tile < NA; ++tile) {
+                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
                     if (col < N) *(float4_t*)(y + col) = acc[tile][j];
                 }
             }
@@ -371,7 +376,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 template <bool UP, int CT>
 __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     constexpr int MC = 16 * CT;                  // activation rows per chunk
-    constexpr int NT = UP ? 128 : 256;           // weight rows per workgroup
+    constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;   // A operands per wavefront
+    constexpr int NT = UP ? 32 * NA : 64 * NA;   // weight rows per workgroup
     constexpr int SPB = MOEMIX_SPB(CT);          // 128-column steps per LDS stage
     extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][SPB * 256 + 16]
     const int tid = threadIdx.x;
@@ -416,19 +422,20 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     const bool int4 = ee.prec == MOE_PREC_INT4G64;
     const int nct = (c.rows + 15) >> 4;          // 16-row tiles that hold any rows
     if (CT >= 8 && nct > 4) {
-        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT), SPB>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT), SPB, NA>(c, ee, out_base);
     } else if (CT >= 4 && nct > 2) {
-        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT), SPB>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT), SPB, NA>(c, ee, out_base);
     } else if (CT >= 2 && nct > 1) {
-        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT), SPB>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT), SPB>(c, ee, out_base);
+        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT), SPB, NA>(c, ee, out_base);
     } else {
-        if (int4) tile_body<UP, true, 1, SPB>(c, ee, out_base); else tile_body<UP, false, 1, SPB>(c, ee, out_base);
+        if (int4) tile_body<UP, true, 1, SPB, NA>(c, ee, out_base); else tile_body<UP, false, 1, SPB, NA>(c, ee, out_base);
     }
 }
 
 template <bool UP, int CT>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
-    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * 4 * 2048;   // + 4 wavefronts x 4 operands x 2 KB
+    constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;
+    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 2048;   // + 4 wavefronts x NA operands x 2 KB
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -467,7 +474,8 @@ MfmaPlan plan_mfma(int P, int d, int f, int E) {
     p.ct = avg <= 16 ? 1 : avg <= 32 ? 2 : avg <= 64 ? 4 : 8;
     // down-projection: split the contraction until there are enough workgroups for 256 compute units
     const int steps = f / kKTile;
-    const int base = ((d + 255) / 256) * (P / (16 * p.ct) + 1);
+    const int down_rows = 64 * (p.ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    const int base = ((d + down_rows - 1) / down_rows) * (P / (16 * p.ct) + 1);
     int best = 1;
     for (int s = 1; s <= 16; ++s)
         if (steps % s == 0 && steps / s >= 2 && base * s <= 1024) best = s;
@@ -482,7 +490,8 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.ex = ex; a.offsets = rows.offsets; a.perm = rows.perm; a.top_k = rows.top_k;
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
-    dim3 grid((f + 127) / 128, chunk_slots(rows, P, E, ct), 1);
+    const int up_rows = 32 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    dim3 grid((f + up_rows - 1) / up_rows, chunk_slots(rows, P, E, ct), 1);
     launch_ct<true>(a, ct, grid, st);
 }
 
@@ -494,7 +503,8 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
     a.status = status;
-    dim3 grid((d + 255) / 256, chunk_slots(rows, P, E, ct), splits);
+    const int down_rows = 64 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    dim3 grid((d + down_rows - 1) / down_rows, chunk_slots(rows, P, E, ct), splits);
     launch_ct<false>(a, ct, grid, st);
 }
 
