@@ -25,6 +25,8 @@ namespace {
 #else
 #define MOEMIX_WLOAD(p) (*(p))
 #endif
+// 4-bit codes are read once per workgroup in whole lines: streamed past the caches' replacement order
+#define MOEMIX_CLOAD(p) __builtin_nontemporal_load(p)
 #ifndef MOEMIX_NA_SMALL
 #define MOEMIX_NA_SMALL 2
 #endif
@@ -241,7 +243,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
         for (int t = 0; t < NA; ++t)
 #pragma unroll
-            for (int hb = 0; hb < 2; ++hb) stg[t][hb] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0);
+            for (int hb = 0; hb < 2; ++hb) stg[t][hb] = MOEMIX_CLOAD((const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0));
     };
     auto stage_to_lds = [&]() {
 #pragma unroll
@@ -478,7 +480,7 @@ MfmaPlan plan_mfma(int P, int d, int f, int E) {
     const int base = ((d + down_rows - 1) / down_rows) * (P / (16 * p.ct) + 1);
     int best = 1;
     for (int s = 1; s <= 16; ++s)
-        if (steps % s == 0 && steps / s >= 2 && base * s <= 1024) best = s;
+        if (steps % s == 0 && steps / s >= 2 && base * s <= 640) best = s;
     p.down_splits = best;
     return p;
 }
