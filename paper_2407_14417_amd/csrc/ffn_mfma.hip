@@ -5,14 +5,15 @@
 //   down: y[s][r, n] = sum_{c in split s} W2[n,c] h[r,c]                      partial sums of the contraction splits
 //
 // One workgroup = 4 wavefronts = one (expert, tile of weight rows, chunk of <= 16*CT activation rows, split).
-// Weights are the A operand of v_mfma_f32_16x16x32_f16 and go from device memory straight into registers, in
-// operand layout: lane (r, c) holds 8 contraction elements of weight row r, so a wavefront's load touches 64
-// contiguous bytes of each of 16 rows, and no weight is ever written to LDS.  4-bit weights are loaded as 32
-// codes per lane and expanded in registers (codes masked into the mantissa of an fp16 constant, the constant
-// subtracted, one packed fp16 multiply-add with the group's scale and zero).  Activations are the B operand:
-// a [16*CT, 128] tile per step of the contraction, double-buffered in LDS and shared by the 4 wavefronts.
-// Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one activation row, so
-// results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
+// Weights are the A operand of v_mfma_f32_16x16x32_f16: lane (r, c) holds 8 contraction elements of weight row r.
+// They are read from device memory in whole 128-byte lines (8 lanes per row, 8 rows per load instruction, streamed)
+// and turned into operand layout through a small wavefront-private LDS region; reading them directly in operand
+// layout would touch 16 half lines per instruction and leaves the memory pipeline, not the matrix cores, in charge.
+// 4-bit weights travel as codes and are expanded in registers (codes masked into the mantissa of an fp16
+// constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and zero).  Activations
+// are the B operand: a [16*CT, 128*SPB] tile per stage of the contraction, double-buffered in LDS and shared by
+// the 4 wavefronts.  Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one
+// activation row, so results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -20,12 +21,7 @@ namespace moemix {
 
 namespace {
 
-#ifdef MOEMIX_NT_WEIGHTS
-#define MOEMIX_WLOAD(p) __builtin_nontemporal_load(p)
-#else
-#define MOEMIX_WLOAD(p) (*(p))
-#endif
-// 4-bit codes are read once per workgroup in whole lines: streamed past the caches' replacement order
+// Weights are read once per workgroup in whole lines: streamed past the caches' replacement order
 #define MOEMIX_CLOAD(p) __builtin_nontemporal_load(p)
 #ifndef MOEMIX_NA_SMALL
 #define MOEMIX_NA_SMALL 2
@@ -158,8 +154,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         }
     };
 
-    // ---- weight rows of this lane: the wavefront owns NT/4 rows from n0 + wave * NT/4, in tiles of 16
-    const uint8_t* wdata[NA];
+    // ---- scales and zeros of this lane's weight rows (4-bit): the wavefront owns NT/4 rows from n0 + wave * NT/4,
+    // in tiles of 16; lane (r16, c4) looks after row r16 of each tile
     const half_t* wscale[NA];
     const half_t* wzero[NA];
 #pragma unroll
@@ -167,15 +163,9 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
         const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
         int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
-        row = row < N ? row : N - 1;                               // rows past the end are loaded from the last row, never stored
-        if (INT4) {
-            wdata[t] = m.data + (size_t)row * (K >> 1) + (c.k_begin >> 1) + c4 * 16;
-            wscale[t] = m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6);
-            wzero[t] = m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6);
-        } else {
-            wdata[t] = m.data + ((size_t)row * K + c.k_begin + c4 * 8) * 2;
-            wscale[t] = wzero[t] = nullptr;
-        }
+        row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
+        wscale[t] = INT4 ? m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
+        wzero[t] = INT4 ? m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
     }
 
     float4_t acc[NA][NCT];
@@ -195,7 +185,6 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     // closes each stage.  Steps are processed in groups of G = max(4, SPB) so that ring slots, the quarter of the
     // scale loads and the place of the barriers are compile-time constants.
     constexpr int G = SPB > 4 ? SPB : 4;
-    uint4_t ring[4][NA];                 // 16-bit: one 32-column sub-step of weights per slot
     uint32_t sz_cur[NA][2], sz_next[NA][2];
     const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
     const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
@@ -209,75 +198,75 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             dst[t][1] = *(const uint32_t*)(wzero[t] + step * 2);
         }
     };
-    // 4-bit codes take a detour through LDS so that device memory is read in whole 128-byte lines: one load
-    // instruction fetches, for 8 weight rows, the 128 bytes (256 columns = two steps) of each row with 8 lanes
-    // per row; the pieces are written to a wavefront-private LDS region (16-byte slots XOR-swizzled by row so that
-    // neither side has bank conflicts) and read back in operand layout, lane (r16, c4) <- slot 4 * (step & 1) + c4.
-    uint4_t stg[NA][2];                  // staged loads of the next pair of steps
-    uint4_t apc[NA][2];                  // codes of the current pair of steps in operand layout
-    uint32_t goff[NA][2];                // per-lane byte offsets of the staged rows inside the code matrix
-    gptr_t cbase[NA];                    // uniform: start of the contraction range in the code matrix
-    uint8_t* const wreg = c.lds + 2 * buf_bytes + wave * (NA * 2048);
-    const int w_wr = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) * 16);
-    const int w_rd = r16 * 128;
-    const int last_pair = (n_steps + 1) / 2 - 1;
-    if (INT4) {
+    // Weights take a detour through LDS so that device memory is read in whole 128-byte lines: one load instruction
+    // fetches, for 8 weight rows, one 128-byte line of each row with 8 lanes per row; the 16-byte pieces are written
+    // to a wavefront-private LDS region (slots XOR-swizzled by row so that neither side has bank conflicts) and read
+    // back in operand layout.  A staging unit is UB bytes of every row: 4-bit, one line = 256 columns = two steps,
+    // lane (r16, c4) takes slot 4 * (step & 1) + c4 as its 32 codes of a step; 16-bit, two lines = 128 columns = one
+    // step, lane (r16, c4) takes slot 4 * sb + c4 as its 8 weights of sub-step sb.
+    constexpr int UL = INT4 ? 1 : 2;     // lines per row and unit
+    constexpr int UB = UL * 128;         // bytes per row and unit
+    constexpr int UA = INT4 ? 2 : 4;     // operand registers (128-bit) per A operand and unit
+    uint4_t stg[NA][2 * UL];             // staged loads of the next unit
+    uint4_t apc[NA][UA];                 // the current unit in operand layout
+    uint32_t goff[NA][2];                // per-lane byte offsets of the staged rows inside the weight matrix
+    gptr_t cbase[NA];                    // uniform: start of the contraction range in the weight matrix
+    uint8_t* const wreg = c.lds + 2 * buf_bytes + wave * (NA * 4096);
+    const int w_wr = (lane >> 3) * UB + (((lane & 7) ^ (lane >> 3)) * 16);
+    const int w_rd = r16 * UB;
+    const int last_unit = INT4 ? (n_steps + 1) / 2 - 1 : n_steps - 1;
 #pragma unroll
-        for (int t = 0; t < NA; ++t) {
-            const int tile = UP ? (t >> 1) : t;
-            const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
-            cbase[t] = scalar_ptr(m.data + (c.k_begin >> 1));
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;
+        const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+        cbase[t] = scalar_ptr(m.data + (INT4 ? (c.k_begin >> 1) : c.k_begin * 2));
 #pragma unroll
-            for (int hb = 0; hb < 2; ++hb) {
-                int row = c.n0 + wave * (NT / 4) + tile * 16 + 8 * hb + (lane >> 3);
-                row = row < N ? row : N - 1;
-                goff[t][hb] = (uint32_t)row * (uint32_t)(K >> 1) + (lane & 7) * 16;
-            }
+        for (int hb = 0; hb < 2; ++hb) {
+            int row = c.n0 + wave * (NT / 4) + tile * 16 + 8 * hb + (lane >> 3);
+            row = row < N ? row : N - 1;                           // rows past the end repeat the last row, never stored
+            goff[t][hb] = (uint32_t)row * (uint32_t)(INT4 ? (K >> 1) : 2 * K) + (lane & 7) * 16;
         }
     }
-    auto load_pair = [&](int pair) {           // a pair past the end repeats the last one (never used)
-        pair = pair < last_pair ? pair : last_pair;
-        // an odd number of steps: the last pair's second half would leave the row only in the last row of the last
-        // split, so the pair is moved back by one step there (its second half is then never used)
-        const int byte0 = (2 * pair + 2 <= n_steps) ? pair * 128 : pair * 128 - 64;
+    auto load_unit = [&](int unit) {           // a unit past the end repeats the last one (never used)
+        unit = unit < last_unit ? unit : last_unit;
+        // 4-bit, odd number of steps: the last pair's second half would leave the row only in the last row of the
+        // last split, so the pair is moved back by one step there (its second half is then never used)
+        const int byte0 = (!INT4 || 2 * unit + 2 <= n_steps) ? unit * UB : unit * UB - 64;
 #pragma unroll
         for (int t = 0; t < NA; ++t)
 #pragma unroll
-            for (int hb = 0; hb < 2; ++hb) stg[t][hb] = MOEMIX_CLOAD((const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0));
+            for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                for (int q = 0; q < UL; ++q)
+                    stg[t][hb * UL + q] = MOEMIX_CLOAD((const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0 + q * 128));
     };
     auto stage_to_lds = [&]() {
 #pragma unroll
         for (int t = 0; t < NA; ++t)
 #pragma unroll
-            for (int hb = 0; hb < 2; ++hb) *(uint4_t*)(wreg + t * 2048 + hb * 1024 + w_wr) = stg[t][hb];
+            for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                for (int q = 0; q < UL; ++q)
+                    *(uint4_t*)(wreg + t * (16 * UB) + hb * (8 * UB) + q * 128 + w_wr) = stg[t][hb * UL + q];
     };
-    auto lds_to_operands = [&](int pair) {
-        // (for the moved-back last pair of an odd range the wanted step sits in the second half)
-        const int shift = (2 * pair + 2 <= n_steps) ? 0 : 4;
+    auto lds_to_operands = [&](int unit) {
+        // (4-bit: for the moved-back last pair of an odd range the wanted step sits in the second half)
+        const int shift = (!INT4 || 2 * unit + 2 <= n_steps) ? 0 : 4;
 #pragma unroll
         for (int t = 0; t < NA; ++t)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int slot = (4 * h + c4 + shift) & 7;
-                apc[t][h] = *(const uint4_t*)(wreg + t * 2048 + w_rd + ((slot ^ (r16 & 7)) * 16));
+            for (int h = 0; h < UA; ++h) {
+                const int slot = (4 * h + c4 + shift) & (8 * UL - 1);
+                // the XOR touches the low three bits of the slot only: a piece stays inside its 128-byte line
+                apc[t][h] = *(const uint4_t*)(wreg + t * (16 * UB) + w_rd + ((slot ^ (r16 & 7)) * 16));
             }
-    };
-    const int last_sub = n_steps * 4 - 1;
-    auto load_w16 = [&](int slot, int sub) {   // sub = sub-step index over the whole contraction range (32 columns each)
-        sub = sub < last_sub ? sub : last_sub;
-#pragma unroll
-        for (int t = 0; t < NA; ++t) ring[slot][t] = MOEMIX_WLOAD((const uint4_t*)(wdata[t] + sub * 64));
     };
 
     load_x(0);
-    if (INT4) {
-        load_sz(sz_cur, 0);
-        load_pair(0);
-        stage_to_lds();
-        load_pair(1);
-    } else {
-        load_w16(0, 0); load_w16(1, 1); load_w16(2, 2);
-    }
+    if (INT4) load_sz(sz_cur, 0);
+    load_unit(0);
+    stage_to_lds();
+    load_unit(1);
     store_x(0);
     load_x(1);
     __syncthreads();
@@ -325,20 +314,22 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     }
                     if (g % 2 == 1 || step == last) {               // the pair is used up: the next one takes its place
                         stage_to_lds();
-                        load_pair((step >> 1) + 2);
+                        load_unit((step >> 1) + 2);
                     }
                 } else {
+                    lds_to_operands(step);
 #pragma unroll
                     for (int sb = 0; sb < 4; ++sb) {
-                        load_w16((sb + 3) & 3, step * 4 + sb + 3);
 #pragma unroll
                         for (int j2 = 0; j2 < NCT; ++j2) {
                             const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
 #pragma unroll
                             for (int t = 0; t < NA; ++t)
-                                acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, ring[sb][t]), b, acc[t][j2]);
+                                acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, apc[t][sb]), b, acc[t][j2]);
                         }
                     }
+                    stage_to_lds();                                 // the step is used up: the next one takes its place
+                    load_unit(step + 2);
                 }
                 if (g % SPB == SPB - 1 || step == last) __syncthreads();
             }
@@ -437,7 +428,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
 template <bool UP, int CT>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;
-    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 2048;   // + 4 wavefronts x NA operands x 2 KB
+    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 4096;   // + 4 wavefronts x NA operands x 4 KB
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
