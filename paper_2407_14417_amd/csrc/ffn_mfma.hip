@@ -43,6 +43,7 @@ struct MfmaArgs {
     int K, N, E;
     int k_per_split;          // contraction elements per split (multiple of 128)
     size_t split_stride;      // elements of y between two splits
+    int unit_bytes;           // LDS bytes per A operand for weight staging: 4096 if any expert is 16-bit, else 2048
     int32_t* status;
 };
 
@@ -98,6 +99,7 @@ struct TileCtx {
     int n0;                  // first weight row of the workgroup
     int k_begin, n_steps;    // contraction range [k_begin, k_begin + 128 n_steps)
     int mc;                  // rows per LDS buffer (16 * ct of the launch)
+    int unit_bytes;          // LDS bytes per A operand of the weight staging regions (2048: 4-bit only, 4096)
     uint8_t* lds;
 };
 
@@ -211,7 +213,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     uint4_t apc[NA][UA];                 // the current unit in operand layout
     uint32_t goff[NA][2];                // per-lane byte offsets of the staged rows inside the weight matrix
     gptr_t cbase[NA];                    // uniform: start of the contraction range in the weight matrix
-    uint8_t* const wreg = c.lds + 2 * buf_bytes + wave * (NA * 4096);
+    uint8_t* const wreg = c.lds + 2 * buf_bytes + wave * (NA * c.unit_bytes);
     const int w_wr = (lane >> 3) * UB + (((lane & 7) ^ (lane >> 3)) * 16);
     const int w_rd = r16 * UB;
     const int last_unit = INT4 ? (n_steps + 1) / 2 - 1 : n_steps - 1;
@@ -398,6 +400,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     c.k_begin = blockIdx.z * a.k_per_split;
     c.n_steps = a.k_per_split / kKTile;
     c.mc = MC;
+    c.unit_bytes = a.unit_bytes;
     c.lds = lds;
     const DevExpert& ee = a.ex.e[e];
     void* out_base = UP ? a.out : (void*)((float*)a.out + blockIdx.z * a.split_stride);
@@ -428,11 +431,13 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
 template <bool UP, int CT>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;
-    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 4096;   // + 4 wavefronts x NA operands x 4 KB
+    // activation stages + 4 wavefronts x NA operands of weight staging
+    const size_t lds_max = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 4096;
+    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds_bytes);
+                                  (int)lds_max);
         configured = true;
     }
     grouped_mfma_kernel<UP, CT><<<grid, 256, lds_bytes, st>>>(a);
@@ -446,6 +451,14 @@ void launch_ct(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
         case 4: launch_one<UP, 4>(a, grid, st); break;
         default: launch_one<UP, 8>(a, grid, st); break;
     }
+}
+
+// Weight staging needs 4 KB of LDS per A operand for 16-bit experts, 2 KB for 4-bit ones.
+int staging_unit_bytes(const DevExperts& ex, int E, const RowMap& rows) {
+    if (rows.direct_expert >= 0) return ex.e[rows.direct_expert].prec == MOE_PREC_INT4G64 ? 2048 : 4096;
+    for (int e = 0; e < E; ++e)
+        if (ex.e[e].prec != MOE_PREC_INT4G64) return 4096;
+    return 2048;
 }
 
 int chunk_slots(const RowMap& rows, int P, int E, int ct) {
@@ -483,6 +496,7 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.ex = ex; a.offsets = rows.offsets; a.perm = rows.perm; a.top_k = rows.top_k;
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
+    a.unit_bytes = staging_unit_bytes(ex, E, rows);
     const int up_rows = 32 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
     dim3 grid((f + up_rows - 1) / up_rows, chunk_slots(rows, P, E, ct), 1);
     launch_ct<true>(a, ct, grid, st);
@@ -496,6 +510,7 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
     a.status = status;
+    a.unit_bytes = staging_unit_bytes(ex, E, rows);
     const int down_rows = 64 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
     dim3 grid((d + down_rows - 1) / down_rows, chunk_slots(rows, P, E, ct), splits);
     launch_ct<false>(a, ct, grid, st);
