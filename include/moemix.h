@@ -134,6 +134,40 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
                       float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream);
 
 /*
+ * Expert-miss path (§3: "a swap space is allocated to transfer experts from the CPU when an expert miss occurs";
+ * §4.1: the copy of an expert is what offloading costs).  Experts of `layer` with resident == 0 live in PINNED
+ * host memory; when the gating network routes a token to one of them it is copied into a slot of a device-side
+ * swap space on `copy_stream` while the resident experts of the same call already compute on `stream`, then the
+ * swapped-in experts run and their contribution is added.  The result equals moe_layer_forward on the same
+ * layer with every expert resident (T > 1: bit for bit; T == 1: the output is rounded to fp16 once more between
+ * the two passes).
+ *   host_experts: HOST array [n_experts]; entry e is read only if layer->experts[e].resident == 0 and then
+ *                 names the expert's matrices (same layouts, `prec` as in the layer) in pinned host memory;
+ *                 a missed expert whose entry has no data keeps the behaviour of moe_layer_forward (left out,
+ *                 MOE_ENOTRESIDENT status bit)
+ *   swap:         device memory, n_slots slots of slot_bytes >= moe_swap_slot_bytes(layer) each, 256-byte aligned;
+ *                 more misses than slots are served in rounds that reuse the slots
+ *   host_idx:     pinned host int32 [T * top_k]: the routing result is handed to the host through it
+ *   copied_event, computed_event: hipEvent_t created by the caller (timing not needed)
+ * Unlike every other call this one waits for `stream` once (the host must see the routing result to know what
+ * to copy), so it cannot be captured into a graph.  *n_missed (host, nullable) = experts copied by this call.
+ */
+typedef struct {
+    const moe_expert* host_experts;
+    void* swap;
+    size_t slot_bytes;
+    int32_t n_slots;
+    int32_t* host_idx;
+    moe_stream_t copy_stream;
+    void* copied_event;
+    void* computed_event;
+} moe_swap;
+size_t moe_swap_slot_bytes(const moe_layer* layer);
+int moe_layer_forward_swap(const moe_layer* layer, const moe_swap* swap, const void* x, int T, void* out,
+                           int32_t* topk_idx_out, float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream,
+                           int32_t* n_missed);
+
+/*
  * Chain of n_layers blocks as in a decoder stack whose non-expert parts are reduced to the 16-bit
  * glue (§3: non-expert layers are always 16-bit):  for each layer
  *   n = fp16_rne( h / sqrt(mean(h^2) + eps) * rms_gain[layer] );   h <- fp16_rne( h + MoE_layer(n) )

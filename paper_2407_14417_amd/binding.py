@@ -23,7 +23,7 @@ STATUS_NOT_RESIDENT = 1 << 3
 EXPORTS = (
     "moe_workspace_bytes", "moe_route", "moe_permute", "moe_expert_ffn_mixed", "moe_layer_forward",
     "moe_chain_forward", "moe_dequant_int4", "moe_quantize_int4", "moe_synth_fill_f16", "moe_read_status",
-    "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan",
+    "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan", "moe_swap_slot_bytes", "moe_layer_forward_swap",
 )
 
 
@@ -58,6 +58,12 @@ class CPlanResult(ctypes.Structure):
                 ("resident_e4", ctypes.c_int32), ("bytes_resident", ctypes.c_uint64)]
 
 
+class CSwap(ctypes.Structure):
+    _fields_ = [("host_experts", ctypes.POINTER(CExpert)), ("swap", ctypes.c_void_p), ("slot_bytes", ctypes.c_size_t),
+                ("n_slots", ctypes.c_int32), ("host_idx", ctypes.c_void_p), ("copy_stream", ctypes.c_void_p),
+                ("copied_event", ctypes.c_void_p), ("computed_event", ctypes.c_void_p)]
+
+
 PREFER_THROUGHPUT, PREFER_QUALITY = 0, 1
 
 _lib = None
@@ -88,10 +94,14 @@ def lib():
         L.moe_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int)]
         L.moe_trace_kernel.argtypes = [i32, vp, vp]
         L.moe_plan.argtypes = [ctypes.POINTER(CPlanRequest), ctypes.POINTER(CPlanResult), vp, vp]
+        L.moe_swap_slot_bytes.argtypes = [LP]
+        L.moe_swap_slot_bytes.restype = sz
+        L.moe_layer_forward_swap.argtypes = [LP, ctypes.POINTER(CSwap), vp, i32, vp, vp, vp, vp, sz, vp,
+                                             ctypes.POINTER(ctypes.c_int32)]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_version.restype = i32
         for name in EXPORTS:
-            if name not in ("moe_workspace_bytes", "moe_last_error", "moe_version"):
+            if name not in ("moe_workspace_bytes", "moe_last_error", "moe_version", "moe_swap_slot_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -189,6 +199,36 @@ def moe_expert_ffn_mixed(layer: Layer, expert: int, x_rows, y, ws) -> None:
 def moe_layer_forward(layer: Layer, x, out, ws, topk_idx_out=None, topk_gate_out=None) -> None:
     _check(lib().moe_layer_forward(ctypes.byref(layer.c), _ptr(x), x.shape[0], _ptr(out), _ptr(topk_idx_out),
                                    _ptr(topk_gate_out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
+
+
+class Swap:
+    """Swap space and host-side expert copies for moe_layer_forward_swap.  `host_experts[e]` is an Expert whose
+    tensors are pinned host tensors (or None for experts that are resident in `layer`)."""
+
+    def __init__(self, layer: Layer, host_experts: Sequence[Optional[Expert]], n_slots: int, n_tokens: int):
+        import torch
+        self.layer, self.host_experts, self.n_slots = layer, list(host_experts), n_slots
+        null = CExpert(PREC_FP16, 0, CMat(None, None, None), CMat(None, None, None), CMat(None, None, None))
+        self._arr = (CExpert * layer.n_experts)(*[e.c() if e is not None else null for e in self.host_experts])
+        self.slot_bytes = int(lib().moe_swap_slot_bytes(ctypes.byref(layer.c)))
+        self.space = torch.empty(max(1, n_slots * self.slot_bytes), dtype=torch.uint8, device="cuda")
+        self.host_idx = torch.empty(n_tokens * layer.top_k, dtype=torch.int32).pin_memory()
+        self.copy_stream = torch.cuda.Stream()
+        self.copied, self.computed = torch.cuda.Event(), torch.cuda.Event()
+        # torch creates the underlying hipEvent_t lazily, on the first record
+        self.copied.record(self.copy_stream)
+        self.computed.record(self.copy_stream)
+        self.c = CSwap(self._arr, _ptr(self.space), self.slot_bytes, n_slots, self.host_idx.data_ptr(),
+                       self.copy_stream.cuda_stream, self.copied.cuda_event, self.computed.cuda_event)
+
+
+def moe_layer_forward_swap(layer: Layer, swap: Swap, x, out, ws, topk_idx_out=None, topk_gate_out=None) -> int:
+    """Returns the number of experts copied in by this call."""
+    missed = ctypes.c_int32(0)
+    _check(lib().moe_layer_forward_swap(ctypes.byref(layer.c), ctypes.byref(swap.c), _ptr(x), x.shape[0], _ptr(out),
+                                        _ptr(topk_idx_out), _ptr(topk_gate_out), _ptr(ws), ws.numel(), _stream(),
+                                        ctypes.byref(missed)))
+    return missed.value
 
 
 class Chain:

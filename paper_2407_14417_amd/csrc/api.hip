@@ -257,6 +257,161 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
                       (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------------- expert-miss path
+
+namespace {
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Bytes of one matrix [out, in] in the given precision: codes or halves, then scales, then zeros, each piece
+// starting on a 256-byte boundary inside a swap slot.
+struct MatBytes {
+    size_t data, scale, zero;
+    size_t total() const { return align256(data) + align256(scale) + align256(zero); }
+};
+MatBytes mat_bytes(int prec, int out, int in) {
+    if (prec == MOE_PREC_INT4G64) {
+        const size_t g = (size_t)out * (in / MOE_GROUP) * 2;
+        return MatBytes{(size_t)out * in / 2, g, g};
+    }
+    return MatBytes{(size_t)out * in * 2, 0, 0};
+}
+
+// Enqueues the host-to-device copies of one matrix into a slot and returns where the pieces landed.
+hipError_t copy_mat(const moe_mat& src, const MatBytes& b, char*& cursor, DevMat* dst, hipStream_t st) {
+    hipError_t e = hipMemcpyAsync(cursor, src.data, b.data, hipMemcpyHostToDevice, st);
+    dst->data = (const uint8_t*)cursor;
+    cursor += align256(b.data);
+    dst->scale = dst->zero = nullptr;
+    if (b.scale && e == hipSuccess) {
+        e = hipMemcpyAsync(cursor, src.scale, b.scale, hipMemcpyHostToDevice, st);
+        dst->scale = (const half_t*)cursor;
+        cursor += align256(b.scale);
+        if (e == hipSuccess) e = hipMemcpyAsync(cursor, src.zero, b.zero, hipMemcpyHostToDevice, st);
+        dst->zero = (const half_t*)cursor;
+        cursor += align256(b.zero);
+    }
+    return e;
+}
+
+// Up- and down-projection of every expert the table marks runnable (deferred ones are skipped silently).
+void run_experts(const moe_layer* L, const DevExperts& table, const half_t* x, int T, const Workspace& w,
+                 const half_t* decode_residual, half_t* out, hipStream_t st) {
+    const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
+    if (T == 1 && decode_shape_ok(d, f)) {
+        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, tuning().up_blocks, st);
+        launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, decode_residual, out, w.status, st);
+        return;
+    }
+    RowMap rows{w.offsets, w.perm, k, -1, 0};
+    const size_t split_stride = (size_t)T * k * d;
+    if (use_mfma(L, T * k)) {
+        const MfmaPlan p = plan_for(L, T * k);
+        launch_ffn_up_mfma(table, E, rows, T * k, x, d, f, w.h, p.ct, w.status, st);
+        launch_ffn_down_mfma(table, E, rows, T * k, w.h, d, f, w.y, p.ct, p.down_splits, split_stride, w.status, st);
+    } else {
+        launch_ffn_up(table, E, rows, x, d, f, w.h, w.status, st);
+        launch_ffn_down(table, E, rows, w.h, d, f, w.y, w.status, st);
+    }
+}
+
+}  // namespace
+
+size_t moe_swap_slot_bytes(const moe_layer* layer) {
+    if (!layer || layer->d_model < 1 || layer->d_ff < 1 || !layer->experts) return 0;
+    size_t worst = 0;
+    for (int e = 0; e < layer->n_experts; ++e) {
+        const int prec = layer->experts[e].prec;
+        const size_t b = 2 * mat_bytes(prec, layer->d_ff, layer->d_model).total() +
+                         mat_bytes(prec, layer->d_model, layer->d_ff).total();
+        worst = b > worst ? b : worst;
+    }
+    return worst;
+}
+
+int moe_layer_forward_swap(const moe_layer* layer, const moe_swap* swap, const void* x, int T, void* out,
+                           int32_t* topk_idx_out, float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream,
+                           int32_t* n_missed) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!swap || !x || !out) return fail(MOE_EINVAL, "moe_layer_forward_swap: NULL argument");
+    if (!swap->host_experts || !swap->swap || !swap->host_idx || !swap->copied_event || !swap->computed_event)
+        return fail(MOE_EINVAL, "moe_layer_forward_swap: incomplete swap descriptor");
+    if (T < 1) return fail(MOE_ESHAPE, "moe_layer_forward_swap: T=%d < 1", T);
+    if (swap->n_slots < 1 || swap->slot_bytes < moe_swap_slot_bytes(layer) || (uintptr_t)swap->swap % 256 ||
+        swap->slot_bytes % 256)
+        return fail(MOE_EWORKSPACE, "swap space: %d slots of %zu bytes, %zu bytes per slot needed (256-byte aligned)",
+                    swap->n_slots, swap->slot_bytes, moe_swap_slot_bytes(layer));
+    Workspace w;
+    if (int rc = check_ws(layer, T, ws, ws_bytes, &w)) return rc;
+    hipStream_t st = (hipStream_t)stream, cst = (hipStream_t)swap->copy_stream;
+    const int d = layer->d_model, f = layer->d_ff, E = layer->n_experts, k = layer->top_k;
+    const half_t* xin = (const half_t*)x;
+
+    // gating, then the one host round trip of this path: which experts were chosen?
+    launch_route(xin, (const half_t*)layer->w_gate, layer->gate_bias, T, d, E, k, w.idx, w.gate, topk_idx_out, topk_gate_out,
+                 w.status, st);
+    hipError_t e = hipMemcpyAsync(swap->host_idx, w.idx, (size_t)T * k * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+    int missed[MOE_MAX_EXPERTS], n_miss = 0;
+    uint32_t seen = 0;
+    for (int i = 0; i < T * k; ++i) {
+        const int32_t ex = swap->host_idx[i];
+        if (ex < 0 || ex >= E || (seen & (1u << ex))) continue;
+        seen |= 1u << ex;
+        const moe_expert& he = swap->host_experts[ex];
+        if (expert_resident(layer->experts[ex]) || !he.w1.data || !he.w3.data || !he.w2.data) continue;
+        if (layer->experts[ex].prec == MOE_PREC_INT4G64 &&
+            (!he.w1.scale || !he.w1.zero || !he.w3.scale || !he.w3.zero || !he.w2.scale || !he.w2.zero))
+            return fail(MOE_EINVAL, "host expert %d: 4-bit matrices need scale and zero", ex);
+        missed[n_miss++] = ex;
+    }
+    if (n_missed) *n_missed = n_miss;
+
+    // pass over the resident experts; the missed ones wait for their copies
+    DevExperts table = device_table(layer);
+    for (int i = 0; i < n_miss; ++i) table.e[missed[i]].resident = kDeferred;
+    const bool decode = T == 1 && decode_shape_ok(d, f);
+    if (!decode) launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
+    run_experts(layer, table, xin, T, w, nullptr, (half_t*)out, st);
+
+    // rounds of at most n_slots copies, each followed by a pass over the experts it brought in
+    for (int first = 0; first < n_miss; first += swap->n_slots) {
+        const int n_round = n_miss - first < swap->n_slots ? n_miss - first : swap->n_slots;
+        DevExperts round = device_table(layer);
+        for (int i = 0; i < E; ++i) round.e[i].resident = kDeferred;
+        if (first > 0) {      // the slots are reused: the pass that read them must have finished
+            e = hipStreamWaitEvent(cst, (hipEvent_t)swap->computed_event, 0);
+            if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+        }
+        for (int i = 0; i < n_round; ++i) {
+            const int ex = missed[first + i];
+            const moe_expert& he = swap->host_experts[ex];
+            const int prec = layer->experts[ex].prec;
+            char* cursor = (char*)swap->swap + (size_t)i * swap->slot_bytes;
+            DevExpert& de = round.e[ex];
+            de.prec = prec;
+            e = copy_mat(he.w1, mat_bytes(prec, f, d), cursor, &de.w1, cst);
+            if (e == hipSuccess) e = copy_mat(he.w3, mat_bytes(prec, f, d), cursor, &de.w3, cst);
+            if (e == hipSuccess) e = copy_mat(he.w2, mat_bytes(prec, d, f), cursor, &de.w2, cst);
+            if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+            de.resident = 1;
+        }
+        e = hipEventRecord((hipEvent_t)swap->copied_event, cst);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st, (hipEvent_t)swap->copied_event, 0);
+        if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+        // at one token the weighted average is fused into the down-projection: this pass adds to the last one's output
+        run_experts(layer, round, xin, T, w, (const half_t*)out, (half_t*)out, st);
+        e = hipEventRecord((hipEvent_t)swap->computed_event, st);
+        if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+    }
+    if (!decode) {
+        const int splits = use_mfma(layer, T * k) ? plan_for(layer, T * k).down_splits : 1;
+        launch_combine(w.y, splits, (size_t)T * k * d, w.gate, w.inv, T, d, k, nullptr, (half_t*)out, st);
+    }
+    return check_hip(st);
+}
+
 int moe_chain_forward(const moe_layer* layers, const void* const* rms_gain, int n_layers, float eps, void* h, int T,
                       int32_t* topk_idx_out, void* ws, size_t ws_bytes, moe_stream_t stream) {
     if (!layers || !rms_gain || !h) return fail(MOE_EINVAL, "moe_chain_forward: NULL argument");

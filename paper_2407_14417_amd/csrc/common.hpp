@@ -26,6 +26,10 @@ struct DevMat {
     const half_t* scale;
     const half_t* zero;
 };
+// `resident` of a device-side table entry: 0 = not in device memory (a launch that meets it raises the status
+// bit and leaves its contribution out), 1 = run it, kDeferred = another launch of the same call runs it (no work,
+// no status bit, nothing written for its rows).
+constexpr int32_t kDeferred = 2;
 struct DevExpert {
     int32_t prec;
     int32_t resident;

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
         const int r0 = __builtin_amdgcn_readfirstlane((int)(int4 ? (l + 8u) / 9u : (l + 31u) / 32u));
         const int r1 = __builtin_amdgcn_readfirstlane((int)(int4 ? (u + 8u) / 9u : (u + 31u) / 32u));
         base += span;
-        if (r0 >= r1) continue;
+        if (r0 >= r1 || ee.resident == kDeferred) continue;
         if (!ee.resident || !ee.w1.data) {
             if (lane == 0) atomicOr(status, kStatusNotResident);
             continue;
@@ -294,6 +294,7 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
     for (int r = 0; r < kDownRows; ++r) acc[r] = 0.0f;
     for (int s = 0; s < k; ++s) {
         const DevExpert& ee = ex.e[idx[s]];
+        if (ee.resident == kDeferred) continue;
         if (!ee.resident || !ee.w2.data) {
             if (threadIdx.x == 0 && blockIdx.x == 0) atomicOr(status, kStatusNotResident);
             continue;

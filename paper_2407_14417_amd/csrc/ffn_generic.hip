@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256) void ffn_up_generic(DevExperts ex, RowMap rows
     if (sp.begin >= sp.end) return;
     const DevExpert& ee = ex.e[sp.e];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (ee.resident == kDeferred) return;
     if (!ee.resident || !ee.w1.data) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(status, kStatusNotResident);
         return;
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(256) void ffn_down_generic(DevExperts ex, RowMap ro
     if (sp.begin >= sp.end) return;
     const DevExpert& ee = ex.e[sp.e];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (ee.resident == kDeferred) return;
     if (!ee.resident || !ee.w2.data) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(status, kStatusNotResident);
         // rows of an expert that cannot run contribute nothing

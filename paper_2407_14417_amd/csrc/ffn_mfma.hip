@@ -404,6 +404,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     c.lds = lds;
     const DevExpert& ee = a.ex.e[e];
     void* out_base = UP ? a.out : (void*)((float*)a.out + blockIdx.z * a.split_stride);
+    if (ee.resident == kDeferred) return;
     if (!(ee.resident && ee.w1.data && ee.w3.data && ee.w2.data)) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(a.status, kStatusNotResident);
         if (!UP) {   // rows of an expert that cannot run contribute nothing
@@ -457,7 +458,7 @@ void launch_ct(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
 int staging_unit_bytes(const DevExperts& ex, int E, const RowMap& rows) {
     if (rows.direct_expert >= 0) return ex.e[rows.direct_expert].prec == MOE_PREC_INT4G64 ? 2048 : 4096;
     for (int e = 0; e < E; ++e)
-        if (ex.e[e].prec != MOE_PREC_INT4G64) return 4096;
+        if (ex.e[e].resident == 1 && ex.e[e].prec != MOE_PREC_INT4G64) return 4096;
     return 2048;
 }
 
