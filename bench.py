@@ -48,6 +48,10 @@ WORKLOADS = {
                     bound="mfma",
                     name="Mixtral-shaped prefill layer: 512 tokens/step, 8 experts top-2, experts 0-1 fp16, 2-7 "
                          "uint4 g64, Zipf(1.2) logit offsets"),
+    "offload": dict(T=1, steps=60, warmup=6, bound="hbm",
+                    name="Mixtral-shaped single MoE layer, batch-1 decode with the expert-miss path: the planner "
+                         "decides from a memory budget which of the 8 experts are 4-bit and which stay in device "
+                         "memory; missed experts are copied from pinned host memory into a swap slot"),
     "chain": dict(T=1, layers=32, steps=40, warmup=4, bound="hbm",
                   name="32-layer chained MoE decode step: 32 x (RMSNorm 1e-5 -> 8-expert top-2 block -> residual), "
                        "1 token, 128 of 256 experts uint4 g64 by seeded random mask"),
@@ -307,6 +311,62 @@ def run_chain_workload(args, wl, mm, workload, torch, np):
     }
 
 
+def run_offload_workload(args, wl, mm, workload, torch, np):
+    """Decode steps through moe_layer_forward_swap.  The planner (moe_plan, quality preference) turns --mem-mb and
+    --num-e4 into the precision mask and the residency of the 8 experts of every pool layer."""
+    steps, warmup = args.steps or wl["steps"], args.warmup if args.warmup is not None else wl["warmup"]
+    pool = args.pool or 2
+    size_e16, size_e4 = 3 * D * F * 2, 3 * (D * F // 2 + 2 * (D * F // 64) * 2)
+    size_ne = E * D * 2
+    slot = size_e16 if args.num_e4 < E else size_e4
+    plan, quantized, resident = mm.moe_plan(int(args.mem_mb * 1e6), size_ne, size_e16, size_e4, E, mm.PREFER_QUALITY,
+                                            args.num_e4, args.seed, args.slots * slot)
+    layers, swaps = [], []
+    for l in range(pool):
+        experts, hosts = [], []
+        for e in range(E):
+            de = workload.device_expert(D, F, args.seed, l, e, bool(quantized[e]))
+            if resident[e]:
+                experts.append(de)
+                hosts.append(None)
+            else:
+                def to_host(m):
+                    return mm.Mat(*[None if t is None else t.cpu().pin_memory() for t in (m.data, m.scale, m.zero)])
+                hosts.append(mm.Expert(de.prec, to_host(de.w1), to_host(de.w3), to_host(de.w2), resident=False))
+                experts.append(mm.Expert(de.prec, None, None, None, resident=False))
+                del de
+        from paper_2407_14417_amd import synth
+        wg = workload.fill_normal((E, D), SIGMA, args.seed, synth.STREAM_WG + 16 * l)
+        layer = mm.Layer(D, F, K, wg, experts, None)
+        layers.append(layer)
+        swaps.append(mm.Swap(layer, hosts, args.slots, 1))
+    n_tok = steps + warmup
+    x_all = workload.device_tokens(n_tok, D, seed=args.seed).reshape(n_tok, 1, D)
+    out_all = torch.empty((n_tok, 1, D), dtype=torch.float16, device="cuda")
+    ws = mm.alloc_workspace(layers[0], 1)
+    torch.cuda.synchronize()
+    misses = 0
+    for i in range(warmup):
+        mm.moe_layer_forward_swap(layers[i % pool], swaps[i % pool], x_all[i], out_all[i], ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(warmup, n_tok):
+        misses += mm.moe_layer_forward_swap(layers[i % pool], swaps[i % pool], x_all[i], out_all[i], ws)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert mm.moe_read_status(ws) == 0
+    return {
+        "value": steps / elapsed, "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3,
+        "config": {"workload": wl["name"], "tokens_per_step": 1, "pool_layers": pool, "launch": "eager",
+                   "mem_budget_MB": args.mem_mb, "num_e4": int(plan.num_e4), "resident_e4": int(plan.resident_e4),
+                   "resident_e16": int(plan.resident_e16), "swap_slots": args.slots,
+                   "resident_MB": plan.bytes_resident / 1e6},
+        "expert_misses_per_token": misses / steps,
+        "roofline": {"bound": "pcie", "kernel": "host-to-device copy of missed experts", "achieved": None, "peak": None,
+                     "unit": "GB/s", "frac": None, "traffic": None},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -317,6 +377,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-tokens", type=int, default=-1, help="oracle sample size (0 = skip, -1 = default)")
+    ap.add_argument("--mem-mb", type=float, default=2000.0, help="offload workload: device memory budget of the layer")
+    ap.add_argument("--num-e4", type=int, default=4, help="offload workload: number of 4-bit experts (of 8)")
+    ap.add_argument("--slots", type=int, default=2, help="offload workload: swap slots")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run a plain device-to-device copy of this many MiB three times: the known-size kernel "
                          "that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -335,6 +398,8 @@ def main() -> int:
     wl = WORKLOADS[args.workload]
     if args.workload == "chain":
         res = run_chain_workload(args, wl, mm, workload, torch, np)
+    elif args.workload == "offload":
+        res = run_offload_workload(args, wl, mm, workload, torch, np)
     else:
         res = run_layer_workload(args, wl, mm, workload, torch, np)
 
@@ -363,7 +428,7 @@ def main() -> int:
     result.update(res)
     cpu_tokens = args.cpu_tokens
     if cpu_tokens < 0:
-        cpu_tokens = {"decode": 48, "batched": 48, "prefill": 64, "chain": 0}[args.workload]
+        cpu_tokens = {"decode": 48, "batched": 48, "prefill": 64, "chain": 0, "offload": 0}[args.workload]
     if cpu_tokens > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.seed, cpu_tokens)
     print(json.dumps(result))
