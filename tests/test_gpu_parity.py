@@ -278,6 +278,23 @@ def test_layer_forward_many_tokens_several_chunks_per_expert(orc):
     assert_ffn_close(out, ref, cfg.name)
 
 
+@pytest.mark.parametrize("E,k,T,zipf", [(32, 8, 500, None), (32, 4, 1500, 1.5), (8, 8, 64, None), (5, 2, 33, 2.0)])
+def test_layer_forward_many_experts_and_slots(orc, E, k, T, zipf):
+    """The limits of the descriptor (32 experts, top-8), experts that receive no row at all (steep Zipf offsets),
+    thousands of grouped rows on a small matrix shape."""
+    cfg = common.Config(f"E{E}k{k}T{T}", 256, 512, E, k, T, tuple(range(0, E, 2)), zipf=zipf)
+    wl = build_workload(cfg, orc)
+    _say(f"layer_forward cfg={cfg.name}")
+    out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
+    ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    counts = np.bincount(ref_idx.reshape(-1), minlength=E)
+    _say(f"rows per expert: min {counts.min()} max {counts.max()} empty {int((counts == 0).sum())}")
+    assert status == 0
+    assert np.array_equal(idx, ref_idx)
+    assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
+    assert_ffn_close(out, ref, cfg.name)
+
+
 def test_layer_forward_single_token_and_odd_token_counts(orc):
     wl = build_workload(MEDIUM, orc)
     layer = device_layer(wl)
