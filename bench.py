@@ -377,6 +377,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-tokens", type=int, default=-1, help="oracle sample size (0 = skip, -1 = default)")
+    ap.add_argument("--int4-experts", default=None,
+                    help="comma-separated expert indices that are 4-bit instead of the workload's own mask "
+                         "(e.g. 0,1,2,3,4,5,6,7 times the all-4-bit pair at batch 1)")
     ap.add_argument("--mem-mb", type=float, default=2000.0, help="offload workload: device memory budget of the layer")
     ap.add_argument("--num-e4", type=int, default=4, help="offload workload: number of 4-bit experts (of 8)")
     ap.add_argument("--slots", type=int, default=2, help="offload workload: swap slots")
@@ -395,7 +398,10 @@ def main() -> int:
 
     mm.lib()                                    # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
-    wl = WORKLOADS[args.workload]
+    wl = dict(WORKLOADS[args.workload])
+    if args.int4_experts is not None and "int4" in wl:       # measurement variant: another precision mask
+        wl["int4"] = tuple(int(e) for e in args.int4_experts.split(",") if e != "")
+        wl["name"] += f" [precision mask overridden: 4-bit experts {list(wl['int4'])}]"
     if args.workload == "chain":
         res = run_chain_workload(args, wl, mm, workload, torch, np)
     elif args.workload == "offload":
@@ -422,7 +428,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 weights / uint4-g64 weights, f32 accumulate",
+        "dtype": "f16 (products of f16 weights and activations accumulated in f32; uint4-g64 weights expanded to f16)",
         "data": "synthetic",
     }
     result.update(res)
