@@ -124,7 +124,14 @@ __device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readf
 // Rows of all routed slots are laid end to end, weighted by their stored bytes (9 units per 4-bit row
 // pair, 32 per 16-bit one), and cut into equal shares, one per wavefront: every wavefront streams the
 // same number of bytes whatever the precision mix.
-constexpr int kUpRowsI4 = 2;   // rows per register buffer of the 4-bit path
+#ifndef MOEMIX_UP_BUFS
+#define MOEMIX_UP_BUFS 2
+#endif
+#ifndef MOEMIX_UP_RB
+#define MOEMIX_UP_RB 2
+#endif
+constexpr int kUpRowsI4 = MOEMIX_UP_RB;
+constexpr uint32_t kMinUnitsPerWave = 100;   // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short   // rows per register buffer of the 4-bit path
 
 template <int NCH>   // d_model / 2048
 __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
@@ -135,9 +142,14 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     // 32-bit arithmetic throughout: total <= 8 slots * 16384 rows * 32 units
     // the wavefront index goes through a scalar register: everything derived from it (row ranges, row base
     // addresses) is then uniform, and the loads below take the scalar-base + 32-bit lane-offset form
-    const uint32_t n_waves = gridDim.x * 4, gw = blockIdx.x * 4 + wave_index();
     uint32_t total = 0;
     for (int s = 0; s < k; ++s) total += (uint32_t)f * (ex.e[idx[s]].prec == MOE_PREC_INT4G64 ? 9u : 32u);
+    // A wavefront needs a dozen rows or so for its load pipeline to reach a steady state.  When the routed
+    // experts are small (all 4-bit), half the workgroups take all the work and the others leave at once: the
+    // launch shape is fixed on the host before the routing result exists, the work is only known here.
+    const uint32_t blocks = (gridDim.x >= 2 && total / (gridDim.x * 4) < kMinUnitsPerWave) ? gridDim.x / 2 : gridDim.x;
+    if (blockIdx.x >= blocks) return;
+    const uint32_t n_waves = blocks * 4, gw = blockIdx.x * 4 + wave_index();
     // balanced cut: the first (total % n_waves) wavefronts take one unit more
     const uint32_t share = total / n_waves, extra = total % n_waves;
     const uint32_t lo = gw * share + (gw < extra ? gw : extra);
@@ -164,10 +176,35 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
             ActI4 act[NCH];
             constexpr int gpr = d / 64;
             constexpr int RB = kUpRowsI4;
-            const uint32_t lane_q = lane * 16, lane_g = (lane >> 1) * 2;   // byte offsets inside a row
+            const uint32_t lane_q = lane * 16;   // byte offset of the lane's codes inside a 1 KB piece of a row
+            // Scales and zeros.  Read as 2-byte (or even 256-byte) pieces per row they cost more device-memory time
+            // than the codes: four extra streams of small scattered requests, measured to cap the kernel at 4.4 TB/s
+            // (6.3 TB/s with the same loads served from cache).  The rows of a matrix lie end to end, so the wavefront
+            // fetches them for G rows at a time as ONE 1 KB run per array (a 128-bit load per lane, like the codes),
+            // parks the run in a wavefront-private LDS region and picks its 2-byte values from there.  The run of group
+            // g is written when group g starts (the wavefront's LDS accesses stay in program order, so group g-1 has
+            // been read by then) and the run of group g+1 is requested at the same moment.
+            constexpr int DPR = 16 * NCH;                        // dwords of scales per row
+            constexpr int G = ((256 / DPR) / RB) * RB;           // rows per group (8 at d = 4096)
+            __shared__ __align__(16) uint8_t sz_lds[4][4][1024];      // [wavefront][array][run]
+            uint8_t* const my_lds = &sz_lds[wave_index()][0][0];
+            const gptr_t szm[4] = {scalar_ptr(ee.w1.scale), scalar_ptr(ee.w1.zero), scalar_ptr(ee.w3.scale),
+                                   scalar_ptr(ee.w3.zero)};
+            uint4_t sg[4];                                       // the run on its way to LDS
+            auto load_group = [&](int rg) {
+                int i = (4 * lane) / DPR;                        // the lane's four dwords belong to row rg + i
+                i = i < G ? i : G - 1;
+                const int row = (rg + i < r1) ? rg + i : r1 - 1; // rows past the end repeat the last one
+                const uint32_t off = (uint32_t)row * (gpr * 2) + (uint32_t)((4 * lane) % DPR) * 4;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) sg[a] = load_stream(at(szm[a], off));
+            };
+            auto publish_group = [&]() {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) *(uint4_t*)(my_lds + a * 1024 + lane * 16) = sg[a];
+            };
             struct Rows {
                 uint4_t pk1[RB][NCH], pk3[RB][NCH];
-                half_t sc1[RB][NCH], zr1[RB][NCH], sc3[RB][NCH], zr3[RB][NCH];
             };
             // RB rows starting at r; rows past the end repeat the last one (loaded, never stored)
             auto load_rows = [&](Rows& B, int r) {
@@ -176,30 +213,29 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                     const int row = (r + i < r1) ? r + i : r1 - 1;
                     const gptr_t q1 = scalar_ptr(ee.w1.data + (size_t)row * (d / 2));      // uniform row bases
                     const gptr_t q3 = scalar_ptr(ee.w3.data + (size_t)row * (d / 2));
-                    const gptr_t s1 = scalar_ptr(ee.w1.scale + (size_t)row * gpr);
-                    const gptr_t z1 = scalar_ptr(ee.w1.zero + (size_t)row * gpr);
-                    const gptr_t s3 = scalar_ptr(ee.w3.scale + (size_t)row * gpr);
-                    const gptr_t z3 = scalar_ptr(ee.w3.zero + (size_t)row * gpr);
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) {
                         B.pk1[i][c] = load_stream(at(q1, lane_q + c * 1024));
                         B.pk3[i][c] = load_stream(at(q3, lane_q + c * 1024));
-                        B.sc1[i][c] = load_half(at(s1, lane_g + c * 64));
-                        B.zr1[i][c] = load_half(at(z1, lane_g + c * 64));
-                        B.sc3[i][c] = load_half(at(s3, lane_g + c * 64));
-                        B.zr3[i][c] = load_half(at(z3, lane_g + c * 64));
                     }
                 }
             };
+            // scale or zero (array a) of row `in_group` of the current group, chunk c, for this lane's group of
+            // columns 32 c + lane / 2
+            const int lane_half = (lane >> 1) * 2;
+            auto pick = [&](int a, int in_group, int c) {
+                return (float)*(const half_t*)(my_lds + a * 1024 + (in_group * DPR + 16 * c) * 4 + lane_half);
+            };
             auto compute_rows = [&](const Rows& B, int r) {
+                const int in_group = (r - r0) % G;
                 float am = 0.0f, bm = 0.0f;   // lane i keeps the totals of row r + i
 #pragma unroll
                 for (int i = 0; i < RB; ++i) {
                     float a = 0.0f, b = 0.0f;
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) {
-                        a += dot_i4(B.pk1[i][c], act[c], (float)B.sc1[i][c], (float)B.zr1[i][c]);
-                        b += dot_i4(B.pk3[i][c], act[c], (float)B.sc3[i][c], (float)B.zr3[i][c]);
+                        a += dot_i4(B.pk1[i][c], act[c], pick(0, in_group + i, c), pick(1, in_group + i, c));
+                        b += dot_i4(B.pk3[i][c], act[c], pick(2, in_group + i, c), pick(3, in_group + i, c));
                     }
                     a = wave_total(a);
                     b = wave_total(b);
@@ -208,23 +244,35 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                 }
                 if (lane < RB && r + lane < r1) hs[r + lane] = (half_t)silu_mul(am, bm);
             };
-            // two register buffers: the loads of the next rows are in flight while the current ones are used
-            // the first weight rows are requested before the token: they come from HBM, the token from L2
-            Rows A, B;
-            load_rows(A, r0);
+            // a ring of NB register buffers: NB - 1 sets of rows are in flight while one is used (a set of 4-bit
+            // rows is used up in well under a microsecond, less than a trip to device memory under load)
+            constexpr int NB = MOEMIX_UP_BUFS;
+            Rows buf[NB];
+#pragma unroll
+            for (int j = 0; j < NB - 1; ++j)
+                if (r0 + j * RB < r1) load_rows(buf[j], r0 + j * RB);
+            load_group(r0);
             __builtin_amdgcn_sched_barrier(0);
+            // the first weight rows are requested before the token: they come from HBM, the token from L2
 #pragma unroll
             for (int c = 0; c < NCH; ++c) load_act_i4(x + c * 2048 + lane * 32, act[c]);
-            for (int r = r0; r < r1; r += 2 * RB) {
-                if (r + RB < r1) load_rows(B, r + RB);
-                __builtin_amdgcn_sched_barrier(0);
-                compute_rows(A, r);
-                __builtin_amdgcn_sched_barrier(0);
-                if (r + RB < r1) {
-                    if (r + 2 * RB < r1) load_rows(A, r + 2 * RB);
-                    __builtin_amdgcn_sched_barrier(0);
-                    compute_rows(B, r + RB);
-                    __builtin_amdgcn_sched_barrier(0);
+            publish_group();
+            load_group(r0 + G);
+            __builtin_amdgcn_sched_barrier(0);
+            for (int r = r0; r < r1; r += NB * RB) {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int rj = r + j * RB;
+                    if (rj < r1) {
+                        if (rj > r0 && (rj - r0) % G == 0) {     // a new group starts: its run goes to LDS, the next is requested
+                            publish_group();
+                            load_group(rj + G);
+                        }
+                        if (r + (j + NB - 1) * RB < r1) load_rows(buf[(j + NB - 1) % NB], r + (j + NB - 1) * RB);
+                        __builtin_amdgcn_sched_barrier(0);
+                        compute_rows(buf[j], rj);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
         } else {
