@@ -21,8 +21,16 @@ namespace moemix {
 
 namespace {
 
-// Weights are read once per workgroup in whole lines: streamed past the caches' replacement order
+// Weights of launches with few activation rows per expert are read once, in whole lines: streamed past the caches'
+// replacement order.  MOEMIX_TEMPORAL_NA: operand count per wavefront from which on lines are kept for sibling chunks;
+// MOEMIX_DIRECT_NCT: activation tiles per chunk from which on 16-bit weights go straight to registers.
 #define MOEMIX_CLOAD(p) __builtin_nontemporal_load(p)
+#ifndef MOEMIX_TEMPORAL_NA
+#define MOEMIX_TEMPORAL_NA 4
+#endif
+#ifndef MOEMIX_DIRECT_NCT
+#define MOEMIX_DIRECT_NCT 8
+#endif
 #ifndef MOEMIX_NA_SMALL
 #define MOEMIX_NA_SMALL 2
 #endif
@@ -240,7 +248,13 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
                 for (int q = 0; q < UL; ++q)
-                    stg[t][hb * UL + q] = MOEMIX_CLOAD((const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0 + q * 128));
+                {
+                    const uint4_t MOEMIX_GLOBAL* src = (const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0 + q * 128);
+                    // launches with many activation rows per expert run several chunks of one expert side by side on
+                    // the same XCD: the second reader of a weight line should find it in L2, so the line is not
+                    // marked as used once there
+                    stg[t][hb * UL + q] = NA >= MOEMIX_TEMPORAL_NA ? *src : MOEMIX_CLOAD(src);
+                }
     };
     auto stage_to_lds = [&]() {
 #pragma unroll
@@ -264,11 +278,38 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             }
     };
 
+    // 16-bit weights of a full chunk (8 activation tiles): the product is bound by LDS traffic, not by the weight
+    // stream, so the A operands skip LDS: lane (r16, c4) loads its 8 weights of every 32-column sub-step
+    // straight from device memory (16 rows x 64 bytes per instruction), one step ahead, into the other half of a
+    // two-step register ring.
+    constexpr bool DIRECT = !INT4 && NCT >= MOEMIX_DIRECT_NCT;
+    uint4_t ad[DIRECT ? 2 : 1][NA][4];
+    uint32_t doff[NA];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;
+        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
+        row = row < N ? row : N - 1;
+        doff[t] = (uint32_t)row * (uint32_t)(2 * K) + c4 * 16;
+    }
+    auto load_direct = [&](int half, int step) {
+        step = step < last ? step : last;
+#pragma unroll
+        for (int t = 0; t < NA; ++t)
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb)
+                ad[half][t][sb] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + step * 256 + sb * 64);
+    };
+
     load_x(0);
     if (INT4) load_sz(sz_cur, 0);
-    load_unit(0);
-    stage_to_lds();
-    load_unit(1);
+    if (DIRECT) {
+        load_direct(0, 0);
+    } else {
+        load_unit(0);
+        stage_to_lds();
+        load_unit(1);
+    }
     store_x(0);
     load_x(1);
     __syncthreads();
@@ -317,6 +358,18 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     if (g % 2 == 1 || step == last) {               // the pair is used up: the next one takes its place
                         stage_to_lds();
                         load_unit((step >> 1) + 2);
+                    }
+                } else if (DIRECT) {
+                    load_direct((g + 1) & 1, step + 1);
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+#pragma unroll
+                        for (int j2 = 0; j2 < NCT; ++j2) {
+                            const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
+#pragma unroll
+                            for (int t = 0; t < NA; ++t)
+                                acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, ad[DIRECT ? (g & 1) : 0][t][sb]), b, acc[t][j2]);
+                        }
                     }
                 } else {
                     lds_to_operands(step);
