@@ -143,6 +143,81 @@ def test_prefill_skewed_sampled_tokens(orc):
     assert np.isfinite(o).all() and (np.abs(o).max(axis=1) > 0).all()
 
 
+def _graph_replays_equal_eager(layer, x_steps, T, k, d, replays=3):
+    """Captures one block call per entry of x_steps in a HIP graph on a side stream (what the benchmark times),
+    replays it several times with eager work and synchronizations in between, and checks every replay bit for
+    bit against the same calls launched eagerly.  Returns the eager outputs and indices."""
+    n = len(x_steps)
+    x_all = torch.stack([dev(x) for x in x_steps])
+    ws = mm.alloc_workspace(layer, T)
+    out_e = torch.empty((n, T, d), dtype=torch.float16, device="cuda")
+    idx_e = torch.empty((n, T, k), dtype=torch.int32, device="cuda")
+    for i in range(n):
+        mm.moe_layer_forward(layer, x_all[i], out_e[i], ws, idx_e[i], None)
+    torch.cuda.synchronize()
+    assert mm.moe_read_status(ws) == 0
+    out_g = torch.empty_like(out_e)
+    idx_g = torch.empty_like(idx_e)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        mm.moe_layer_forward(layer, x_all[0], out_g[0], ws, idx_g[0], None)     # warm-up outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(n):
+                mm.moe_layer_forward(layer, x_all[i], out_g[i], ws, idx_g[i], None)
+        for rep in range(replays):
+            out_g.zero_()                                   # eager work between the replays
+            idx_g.fill_(-1)
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            _say(f"graph replay {rep}")
+            assert torch.equal(idx_g, idx_e), f"replay {rep}: indices differ from the eager launches"
+            assert torch.equal(out_g, out_e), f"replay {rep}: outputs differ from the eager launches"
+            assert mm.moe_read_status(ws) == 0
+    torch.cuda.synchronize()
+    return out_e, idx_e
+
+
+def test_decode_graph_replay_equals_eager_and_oracle(orc, decode_layer):
+    """Batch-1 decode in the benchmark's launch configuration: several steps in one HIP graph, replayed."""
+    cfg = DECODE
+    wg = common.gate_matrix(cfg)
+    steps = []
+    for retry in range(64):
+        x = synth.normal_f16((1, cfg.d), 1.0, cfg.seed, synth.x_stream(100 + retry))
+        lg = np.sort(common.logits_f64(x, wg, None)[0])[::-1]
+        if min(lg[0] - lg[1], lg[1] - lg[2]) >= 1e-3:
+            steps.append(x)
+        if len(steps) == 6:
+            break
+    assert len(steps) == 6
+    out_e, idx_e = _graph_replays_equal_eager(decode_layer, steps, 1, cfg.k, cfg.d)
+    for i in (0, 5):
+        ref_idx, ref_gate = orc.route(steps[i], wg, cfg.k)
+        assert np.array_equal(idx_e[i].cpu().numpy(), ref_idx)
+        ref = _oracle_tokens(orc, cfg, steps[i], wg, None, ref_idx, ref_gate, [0])
+        assert_ffn_close(out_e[i].cpu().numpy(), ref, f"decode graph step {i}")
+
+
+def test_batched_graph_replay_equals_eager(orc):
+    """16 tokens, all experts 4-bit (matrix-core path: grouping, split down-projection, weighted average) in one
+    HIP graph, replayed; one step is checked against the oracle on a sample of tokens."""
+    cfg = BATCHED
+    layer = workload.device_layer(cfg.d, cfg.f, cfg.E, cfg.k, cfg.int4_experts, seed=cfg.seed, router="uniform")
+    wg = common.gate_matrix(cfg)
+    x0 = common.tokens_with_margin(cfg, wg, None)
+    steps = [x0, np.ascontiguousarray(x0[::-1]), np.ascontiguousarray(np.roll(x0, 5, axis=0))]
+    out_e, idx_e = _graph_replays_equal_eager(layer, steps, cfg.T, cfg.k, cfg.d)
+    x = steps[1]
+    ref_idx, ref_gate = orc.route(x, wg, cfg.k)
+    assert np.array_equal(idx_e[1].cpu().numpy(), ref_idx)
+    sample = [0, 7, 15]
+    ref = _oracle_tokens(orc, cfg, x, wg, None, ref_idx, ref_gate, sample)
+    assert_ffn_close(out_e[1].cpu().numpy()[sample], ref, "batched graph step 1 sample")
+
+
 def test_chain_32_layers_decode(orc):
     """32 x (RMSNorm -> MoE -> residual), T=1, 256 experts of which a seeded random half is 4-bit (57.8 GB
     resident).  The oracle regenerates only the routed experts.  Teacher-forced per layer; the free-running
