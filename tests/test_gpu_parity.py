@@ -479,3 +479,25 @@ def test_decode_path_non_resident_and_chain(orc):
     assert mm.moe_read_status(ws) == 0
     assert np.array_equal(idx_out.cpu().numpy(), np.stack(idxs))
     assert_ffn_close(h.cpu().numpy(), hs[-1], "decode chain")
+    # the same chain captured in a HIP graph (the benchmark's launch configuration), replayed: every replay
+    # starts from a fresh copy of the input and must end in the eager result, bit for bit
+    h_eager = h.clone()
+    chain = mm.Chain(layers, [dev(g)] * 3)
+    x_dev = dev(x)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        h.copy_(x_dev)
+        mm.moe_chain_forward(chain, eps, h, ws, idx_out)                # warm-up outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            mm.moe_chain_forward(chain, eps, h, ws, idx_out)
+        for rep in range(3):
+            h.copy_(x_dev)
+            idx_out.fill_(-1)
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            _say(f"chain graph replay {rep}")
+            assert torch.equal(h, h_eager) and np.array_equal(idx_out.cpu().numpy(), np.stack(idxs))
+    torch.cuda.synchronize()
