@@ -14,6 +14,8 @@
 // are the B operand: a [16*CT, 128*SPB] tile per stage of the contraction, double-buffered in LDS and shared by
 // the 4 wavefronts.  Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one
 // activation row, so results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
+#include <atomic>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -488,11 +490,16 @@ void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     // activation stages + 4 wavefronts x NA operands of weight staging
     const size_t lds_max = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 4096;
     const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
-    static bool configured = false;
-    if (!configured) {
+    // the attribute belongs to (kernel, device): set it once per device of the process (bit d of the mask; devices
+    // past the 64th set it on every launch)
+    static std::atomic<unsigned long long> configured{0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;
+    if (!(configured.load(std::memory_order_relaxed) & bit) || !bit) {
         (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)lds_max);
-        configured = true;
+        configured.fetch_or(bit, std::memory_order_relaxed);
     }
     grouped_mfma_kernel<UP, CT><<<grid, 256, lds_bytes, st>>>(a);
 }
