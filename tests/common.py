@@ -150,6 +150,8 @@ def tokens_with_margin(cfg: Config, wg: np.ndarray, bias: Optional[np.ndarray], 
     for retry in range(1, 64):
         l = np.sort(logits_f64(x, wg, bias), axis=1)[:, ::-1]
         top = l[:, : min(cfg.k + 1, cfg.E)]
+        if top.shape[1] < 2:                      # a single expert: nothing to tell apart
+            return x
         bad = np.where((top[:, :-1] - top[:, 1:]).min(axis=1) < margin)[0]
         if bad.size == 0:
             return x

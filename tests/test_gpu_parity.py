@@ -295,6 +295,37 @@ def test_layer_forward_many_experts_and_slots(orc, E, k, T, zipf):
     assert_ffn_close(out, ref, cfg.name)
 
 
+def _random_configs(n, seed=20240719):
+    """Seeded draw of block shapes inside the library's limits: d_model and d_ff multiples of 64 (some multiples
+    of 128: matrix-core path, the others: shape-agnostic kernels), 1-12 experts, top-1..4, 1-70 tokens, a random
+    precision mask, optional Zipf offsets."""
+    rng = np.random.default_rng(seed)
+    cfgs = []
+    for i in range(n):
+        d = int(rng.choice([64, 128, 192, 256, 384, 512, 640, 768, 1024]))
+        f = int(rng.choice([64, 128, 320, 384, 512, 896, 1024, 1536]))
+        E = int(rng.integers(1, 13))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        T = int(rng.choice([1, 2, 3, 7, 16, 17, 31, 33, 48, 70]))
+        mask = tuple(int(e) for e in range(E) if rng.random() < 0.5)
+        zipf = float(rng.choice([0.0, 1.2, 2.0]))
+        cfgs.append(common.Config(f"rand{i}_d{d}_f{f}_E{E}_k{k}_T{T}", d, f, E, k, T, mask, seed=100 + i,
+                                  zipf=zipf or None))
+    return cfgs
+
+
+@pytest.mark.parametrize("cfg", _random_configs(20), ids=lambda c: c.name)
+def test_layer_forward_random_shapes(orc, cfg):
+    wl = build_workload(cfg, orc)
+    _say(f"layer_forward cfg={cfg.name} int4={cfg.int4_experts} zipf={cfg.zipf}")
+    out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
+    ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    assert status == 0
+    assert np.array_equal(idx, ref_idx)
+    assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
+    assert_ffn_close(out, ref, cfg.name)
+
+
 def test_layer_forward_single_token_and_odd_token_counts(orc):
     wl = build_workload(MEDIUM, orc)
     layer = device_layer(wl)
