@@ -485,6 +485,37 @@ def test_decode_path_small_shape_all_precision_mixes(orc, k):
     assert len(kinds) >= (3 if k == 2 else 2)
 
 
+@pytest.mark.parametrize("d,f,E,k,mask", [(2048, 2048, 3, 1, (0,)), (2048, 6144, 5, 3, (1, 2, 4)), (4096, 2048, 2, 2, (1,)),
+                                          (2048, 4096, 4, 4, ()), (2048, 2048, 6, 2, (0, 1, 2, 3, 4, 5))])
+def test_decode_path_other_shapes(orc, d, f, E, k, mask):
+    """Other shapes the batch-1 kernels take (d_model and d_ff multiples of 2048): one to six experts, top-1..4,
+    all-16-bit, all-4-bit and mixed tables, three tokens each."""
+    cfg = common.Config(f"dec_d{d}_f{f}_E{E}_k{k}", d, f, E, k, 1, mask, seed=7)
+    wl = build_workload(cfg, orc)
+    layer = device_layer(wl)
+    ws = mm.alloc_workspace(layer, 1)
+    done = 0
+    for retry in range(12):
+        x = synth.normal_f16((1, d), 1.0, cfg.seed, synth.x_stream(retry))
+        lg = np.sort(common.logits_f64(x, wl.wg, None)[0])[::-1]
+        if k < E and (lg[:k] - lg[1:k + 1]).min() < 1e-3 or k == E and k > 1 and (lg[:-1] - lg[1:]).min() < 1e-3:
+            continue
+        _say(f"decode {cfg.name} token stream {retry}")
+        out = torch.empty((1, d), dtype=torch.float16, device="cuda")
+        idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        gate = torch.empty((1, k), dtype=torch.float32, device="cuda")
+        mm.moe_layer_forward(layer, dev(x), out, ws, idx, gate)
+        assert mm.moe_read_status(ws) == 0
+        ref, ref_idx, ref_gate = orc.layer_forward(x, wl.wg, wl.experts, k)
+        assert np.array_equal(idx.cpu().numpy(), ref_idx)
+        assert np.allclose(gate.cpu().numpy(), ref_gate, rtol=0, atol=GATE_ATOL)
+        assert_ffn_close(out.cpu().numpy(), ref, f"{cfg.name} retry={retry}")
+        done += 1
+        if done == 3:
+            break
+    assert done == 3
+
+
 def test_decode_path_non_resident_and_chain(orc):
     cfg = common.DECODE_SMALL
     wl = build_workload(cfg, orc)
