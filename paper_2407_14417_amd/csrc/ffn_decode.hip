@@ -130,8 +130,8 @@ __device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readf
 #ifndef MOEMIX_UP_RB
 #define MOEMIX_UP_RB 2
 #endif
-constexpr int kUpRowsI4 = MOEMIX_UP_RB;
-constexpr uint32_t kMinUnitsPerWave = 100;   // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short   // rows per register buffer of the 4-bit path
+constexpr int kUpRowsI4 = MOEMIX_UP_RB;         // rows per register buffer of the 4-bit path
+constexpr uint32_t kMinUnitsPerWave = 100;      // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short
 
 template <int NCH>   // d_model / 2048
 __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
