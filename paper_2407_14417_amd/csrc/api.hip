@@ -233,11 +233,21 @@ int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows,
     const DevExperts table = device_table(layer);
     RowMap rows{nullptr, nullptr, layer->top_k, expert, n};
     const int d = layer->d_model, f = layer->d_ff;
+    launch_zero_words(w.status, 1, st);   // the status word describes this call
     if (use_mfma(layer, n)) {
-        int ct = plan_mfma(n, d, f, 1).ct;        // all n rows belong to the one expert
-        if (tuning().mfma_ct) ct = tuning().mfma_ct;
-        launch_ffn_up_mfma(table, layer->n_experts, rows, n, (const half_t*)x_rows, d, f, w.h, ct, w.status, st);
-        launch_ffn_down_mfma(table, layer->n_experts, rows, n, w.h, d, f, y, ct, 1, 0, w.status, st);
+        MfmaPlan p = plan_mfma(n, d, f, 1);       // all n rows belong to the one expert
+        if (tuning().mfma_ct) p.ct = tuning().mfma_ct;
+        launch_ffn_up_mfma(table, layer->n_experts, rows, n, (const half_t*)x_rows, d, f, w.h, p.ct, w.status, st);
+        // few rows: the contraction of the down-projection is split over as many workgroups as the workspace's
+        // partial-result region was sized for, and the partials are added in order
+        const int splits = p.down_splits < w.y_splits ? p.down_splits : w.y_splits;
+        if (splits > 1) {
+            const size_t stride = (size_t)n * d;
+            launch_ffn_down_mfma(table, layer->n_experts, rows, n, w.h, d, f, w.y, p.ct, splits, stride, w.status, st);
+            launch_reduce_splits(w.y, splits, stride, stride, y, st);
+        } else {
+            launch_ffn_down_mfma(table, layer->n_experts, rows, n, w.h, d, f, y, p.ct, 1, 0, w.status, st);
+        }
     } else {
         launch_ffn_up(table, layer->n_experts, rows, (const half_t*)x_rows, d, f, w.h, w.status, st);
         launch_ffn_down(table, layer->n_experts, rows, w.h, d, f, y, w.status, st);

@@ -41,19 +41,21 @@ void launch_combine(const float* y, int splits, size_t split_stride, const float
     combine_kernel<<<grid, 256, 0, st>>>(y, splits, split_stride, gate, inv, d, k, residual, out);
 }
 
-__global__ __launch_bounds__(256) void reduce_splits_kernel(float* __restrict__ y, int splits, size_t split_stride, size_t n4) {
+// dst[i] = sum_p y[p][i], partials added in order
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ y, int splits, size_t split_stride,
+                                                             size_t n4, float* __restrict__ dst) {
     for (size_t i = blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
         float4_t v = ((const float4_t*)y)[i];
         for (int p = 1; p < splits; ++p) v += *(const float4_t*)(y + p * split_stride + i * 4);
-        ((float4_t*)y)[i] = v;
+        ((float4_t*)dst)[i] = v;
     }
 }
 
-void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, hipStream_t st) {
-    if (splits < 2 || n == 0) return;
+void launch_reduce_splits(const float* y, int splits, size_t split_stride, size_t n, float* dst, hipStream_t st) {
+    if (n == 0) return;
     const size_t n4 = n / 4;
     const int blocks = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
-    reduce_splits_kernel<<<blocks, 256, 0, st>>>(y, splits, split_stride, n4);
+    reduce_splits_kernel<<<blocks, 256, 0, st>>>(y, splits, split_stride, n4, dst);
 }
 
 // Fill kernel used instead of a memset node so that every launch sequence stays graph-capturable.

@@ -56,8 +56,8 @@ void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* g
 // p over the `splits` partial results, `split_stride` elements apart.
 void launch_combine(const float* y, int splits, size_t split_stride, const float* gate, const int32_t* inv, int T, int d,
                     int k, const half_t* residual, half_t* out, hipStream_t st);
-// y[r, :] = sum_p y[p][r, :] for r < n (in place, into the first partial)
-void launch_reduce_splits(float* y, int splits, size_t split_stride, size_t n, hipStream_t st);
+// dst[i] = sum_p y[p][i] for i < n (n a multiple of 4), p over the `splits` partial results `split_stride` elements apart
+void launch_reduce_splits(const float* y, int splits, size_t split_stride, size_t n, float* dst, hipStream_t st);
 void launch_zero_words(int32_t* p, int n, hipStream_t st);
 
 void launch_dequant_int4(const DevMat& m, int out, int in, half_t* w, hipStream_t st);
