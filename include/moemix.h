@@ -28,8 +28,8 @@
  *     consecutive columns of one row share an fp16 scale and an fp16 zero,
  *     two codes per byte, the even column in the low nibble;
  *     dequantized weight = fp16_rne( fp32(code) * fp32(scale) + fp32(zero) ).
- *   - d_model and d_ff must be multiples of 64; n_experts <= MOE_MAX_EXPERTS;
- *     1 <= top_k <= min(n_experts, MOE_MAX_TOPK).
+ *   - d_model and d_ff must be multiples of 64, d_model <= 8192, d_ff <= 16384 (else MOE_ESHAPE);
+ *     n_experts <= MOE_MAX_EXPERTS; 1 <= top_k <= min(n_experts, MOE_MAX_TOPK).
  */
 #ifndef MOEMIX_H
 #define MOEMIX_H
@@ -115,6 +115,7 @@ int moe_permute(const moe_layer* layer, const int32_t* topk_idx, int T, int32_t*
  * its descriptor names (§3), 4-bit weights being dequantized inside the matrix kernels:
  *   y[i,:] = W2 ( silu(W1 x_i) * (W3 x_i) )                        fp32 accumulation
  * x_rows: device fp16 [n, d_model]; y: device fp32 [n, d_model] (overwritten).
+ * ws: at least moe_workspace_bytes(layer, ceil(n / top_k)) bytes (the hidden rows live there).
  * Fails with MOE_ENOTRESIDENT on the host if the expert is not resident.
  */
 int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows, int n, float* y, void* ws,
@@ -134,8 +135,8 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
                       float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream);
 
 /*
- * Expert-miss path (§3: "a swap space is allocated to transfer experts from the CPU when an expert miss occurs";
- * §4.1: the copy of an expert is what offloading costs).  Experts of `layer` with resident == 0 live in PINNED
+ * Expert-miss path (§3: device memory is set aside as a swap space that receives an expert from the host when
+ * a token is routed to an expert that is not on the device; §4.1: the copy of an expert is what offloading costs).  Experts of `layer` with resident == 0 live in PINNED
  * host memory; when the gating network routes a token to one of them it is copied into a slot of a device-side
  * swap space on `copy_stream` while the resident experts of the same call already compute on `stream`, then the
  * swapped-in experts run and their contribution is added.  The result equals moe_layer_forward on the same
@@ -180,7 +181,7 @@ int moe_chain_forward(const moe_layer* layers, const void* const* rms_gain, int 
 
 /*
  * Dequantize one 4-bit matrix to fp16 (check hook for the format; also what a switch of an expert
- * from 4-bit to 16-bit form needs, §3 "partial reconfiguration"):
+ * from 4-bit to 16-bit form needs when the table is re-planned for new constraints, §3):
  *   w_fp16[r,c] = fp16_rne( fp32(code[r,c]) * fp32(scale[r,c/64]) + fp32(zero[r,c/64]) )
  * m: 4-bit matrix [out,in]; w_fp16: device fp16 [out,in].
  */
@@ -188,7 +189,7 @@ int moe_dequant_int4(const moe_mat* m, int out, int in, void* w_fp16, moe_stream
 
 /*
  * Quantize one fp16 matrix to the 4-bit form on the device (switching an expert from 16-bit to
- * 4-bit without a host round trip, §3 "switching between quantized and 16-bit formats").
+ * 4-bit without a host round trip; §3 has experts change format when the constraints change).
  * Per group of 64 columns: zero = min; scale = fp16_rne((fp32(max) - fp32(min)) / 15);
  * code = clamp(rint((fp32(w) - fp32(zero)) / fp32(scale)), 0, 15), all codes 0 when scale == 0.
  * w_fp16: device fp16 [out,in]; packed: device uint8 [out,in/2]; scale, zero: device fp16 [out,in/64].

@@ -1,5 +1,5 @@
 // The 4-bit weight format on the device: dequantizer (check hook, 4-bit -> 16-bit switch),
-// quantizer (16-bit -> 4-bit switch, paper §3 "partial reconfiguration"), and the seeded
+// quantizer (16-bit -> 4-bit switch when the expert table is re-planned, paper §3), and the seeded
 // synthetic-tensor fill.
 #include "common.hpp"
 #include "kernels.hpp"
