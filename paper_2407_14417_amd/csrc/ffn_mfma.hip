@@ -473,15 +473,22 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     }
     const bool int4 = ee.prec == MOE_PREC_INT4G64;
     const int nct = (c.rows + 15) >> 4;          // 16-row tiles that hold any rows
-    if (CT >= 8 && nct > 4) {
-        if (int4) tile_body<UP, true, (CT >= 8 ? 8 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 8 ? 8 : CT), SPB, NA>(c, ee, out_base);
-    } else if (CT >= 4 && nct > 2) {
-        if (int4) tile_body<UP, true, (CT >= 4 ? 4 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 4 ? 4 : CT), SPB, NA>(c, ee, out_base);
-    } else if (CT >= 2 && nct > 1) {
-        if (int4) tile_body<UP, true, (CT >= 2 ? 2 : CT), SPB, NA>(c, ee, out_base); else tile_body<UP, false, (CT >= 2 ? 2 : CT), SPB, NA>(c, ee, out_base);
-    } else {
-        if (int4) tile_body<UP, true, 1, SPB, NA>(c, ee, out_base); else tile_body<UP, false, 1, SPB, NA>(c, ee, out_base);
-    }
+    // the straight-line body for exactly the chunk's tiles where the launch can have that many (the clamp keeps
+    // the smaller launches from instantiating bodies they never run)
+#define MOEMIX_BODY(n)                                                                                          \
+    do {                                                                                                        \
+        if (int4) tile_body<UP, true, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                        \
+        else tile_body<UP, false, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                            \
+    } while (0)
+    if (CT >= 8 && nct > 7) MOEMIX_BODY(8);
+    else if (CT >= 8 && nct > 6) MOEMIX_BODY(7);
+    else if (CT >= 8 && nct > 5) MOEMIX_BODY(6);
+    else if (CT >= 8 && nct > 4) MOEMIX_BODY(5);
+    else if (CT >= 4 && nct > 3) MOEMIX_BODY(4);
+    else if (CT >= 4 && nct > 2) MOEMIX_BODY(3);
+    else if (CT >= 2 && nct > 1) MOEMIX_BODY(2);
+    else MOEMIX_BODY(1);
+#undef MOEMIX_BODY
 }
 
 template <bool UP, int CT>

@@ -186,10 +186,11 @@ def test_expert_ffn_both_precisions(orc, cfg, n):
         assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n={n} e={e}")
 
 
-@pytest.mark.parametrize("n", [2, 16, 17, 33, 130, 300])
+@pytest.mark.parametrize("n", [2, 16, 17, 33, 40, 72, 90, 105, 130, 300])
 def test_expert_ffn_odd_steps_ragged_tiles_many_chunks(orc, n):
     """Matrix-core path: odd step counts (the last pair of 4-bit steps is fetched one step back), a ragged tile of
-    weight rows, row counts from one partial 16-row tile to three 128-row chunks."""
+    weight rows, row counts from one partial 16-row tile to three 128-row chunks; 40, 72, 90 and 105 rows run the
+    bodies for exactly 3, 5, 6 and 7 activation tiles."""
     cfg = ODD_STEPS
     wl = build_workload(cfg, orc, experts_needed=(0, 1))
     assert wl.experts[0].int4 and not wl.experts[1].int4
