@@ -118,7 +118,7 @@ struct TileCtx {
 // chunks of many activation rows (each B operand read from LDS feeds 4 products), NA = 2 when a chunk holds at
 // most 32 rows: the kernel is then bound by the expansion of the codes, and half the registers per wavefront
 // buy twice the wavefronts per SIMD to hide its latencies.
-// NCT = 16-row activation tiles computed (a power of two >= the tiles that hold rows), so the inner loops are
+// NCT = 16-row activation tiles computed (exactly the tiles that hold rows), so the inner loops are
 // straight-line code.  SPB = 128-column steps per LDS stage (and per barrier): a launch with few activation
 // rows per chunk stages more columns at a time, so that the LDS buffers always hold 128 x 128 elements.
 template <bool UP, bool INT4, int NCT, int SPB, int NA>
