@@ -422,6 +422,195 @@ int orc_chain_layer(uint16_t* h, int T, int d, int f, int E, int k, const uint16
     return rc;
 }
 
+/* ---------------------------------------------------------------- second mode: fp32 accumulators, 16-bit intermediates
+ *
+ * The paper does not say in what precision the block accumulates or which intermediates a "16-bit" model
+ * rounds (§3 only fixes that weights are 16-bit or 4-bit).  The functions above take the most precise reading
+ * (double, nothing rounded).  The functions below are the same definitions under the other reading: every
+ * accumulator is an fp32 variable added to in index order, the hidden row silu(a)*b and the block output are
+ * rounded to fp16, transcendental functions are the fp32 library ones.  They exist to MEASURE how far a
+ * faithful 16-bit implementation may sit from the double result (one block, and a chain of blocks in which the
+ * deviations feed back); nothing is compared against them for correctness.
+ * exact_weights != 0: a 4-bit weight enters the products as the fp32 value code * scale + zero (the product is
+ * exact, the sum rounded to fp32 once) instead of its fp16 rounding -- what an implementation does that never
+ * materialises the dequantized weight.
+ * Pins: agreement with the double functions within the textbook forward-error bound of fp32 summation plus
+ * the stated fp16 roundings; bit-equality with them on inputs where every operation is exact.
+ */
+
+static void mat_row_f32(const orc_mat* m, int prec_int4, int exact_weights, int r, int in, float* row) {
+    if (prec_int4) {
+        const int groups = in / ORC_GROUP;
+        const uint8_t* q = (const uint8_t*)m->data + (size_t)r * (in / 2);
+        const uint16_t* sr = m->scale + (size_t)r * groups;
+        const uint16_t* zr = m->zero + (size_t)r * groups;
+        for (int c = 0; c < in; ++c) {
+            float s = orc_half_to_float(sr[c / ORC_GROUP]);
+            float z = orc_half_to_float(zr[c / ORC_GROUP]);
+            volatile float prod = (float)nibble_at(q, c) * s;
+            volatile float sum = prod + z;
+            row[c] = exact_weights ? sum : orc_half_to_float(orc_float_to_half(sum));
+        }
+    } else {
+        const uint16_t* src = (const uint16_t*)m->data + (size_t)r * in;
+        for (int c = 0; c < in; ++c) row[c] = orc_half_to_float(src[c]);
+    }
+}
+
+/* y: fp32 [n,d]; h_out: optional fp16 [n,f] (the rounded hidden rows). */
+int orc_expert_ffn_f32(int prec_int4, const orc_mat* w1, const orc_mat* w3, const orc_mat* w2,
+                       const uint16_t* x_rows, int n, int d, int f, int exact_weights, float* y, uint16_t* h_out) {
+    if (n < 0 || d < 1 || f < 1) return -1;
+    if (prec_int4 && (d % ORC_GROUP != 0 || f % ORC_GROUP != 0)) return -1;
+    if (n == 0) return 0;
+    float* xf = (float*)malloc(sizeof(float) * (size_t)n * d);
+    float* h = (float*)malloc(sizeof(float) * (size_t)n * f);
+    for (size_t i = 0; i < (size_t)n * d; ++i) xf[i] = orc_half_to_float(x_rows[i]);
+#pragma omp parallel
+    {
+        float* row1 = (float*)malloc(sizeof(float) * (size_t)d);
+        float* row3 = (float*)malloc(sizeof(float) * (size_t)d);
+#pragma omp for schedule(static)
+        for (int r = 0; r < f; ++r) {
+            mat_row_f32(w1, prec_int4, exact_weights, r, d, row1);
+            mat_row_f32(w3, prec_int4, exact_weights, r, d, row3);
+            for (int i = 0; i < n; ++i) {
+                volatile float a = 0.0f, b = 0.0f;
+                for (int j = 0; j < d; ++j) {
+                    volatile float pa = row1[j] * xf[(size_t)i * d + j];
+                    volatile float pb = row3[j] * xf[(size_t)i * d + j];
+                    a = a + pa;
+                    b = b + pb;
+                }
+                volatile float e = expf(-a);
+                volatile float den = 1.0f + e;
+                volatile float sg = a / den;
+                volatile float hv = sg * b;
+                uint16_t hb = orc_float_to_half(hv);
+                h[(size_t)i * f + r] = orc_half_to_float(hb);
+                if (h_out) h_out[(size_t)i * f + r] = hb;
+            }
+        }
+        free(row1);
+        free(row3);
+        float* row2 = (float*)malloc(sizeof(float) * (size_t)f);
+#pragma omp for schedule(static)
+        for (int r = 0; r < d; ++r) {
+            mat_row_f32(w2, prec_int4, exact_weights, r, f, row2);
+            for (int i = 0; i < n; ++i) {
+                volatile float acc = 0.0f;
+                for (int j = 0; j < f; ++j) {
+                    volatile float p = row2[j] * h[(size_t)i * f + j];
+                    acc = acc + p;
+                }
+                y[(size_t)i * d + r] = acc;
+            }
+        }
+        free(row2);
+    }
+    free(xf);
+    free(h);
+    return 0;
+}
+
+/* Gating in fp32: logits accumulated in index order, selection as in orc_route, gates with expf. */
+int orc_route_f32(const uint16_t* x, int T, int d, const uint16_t* wg, const float* bias, int E, int k,
+                  int32_t* idx, float* gate) {
+    if (T < 0 || d < 1 || E < 1 || k < 1 || k > E) return -1;
+    for (int t = 0; t < T; ++t) {
+        float* l = (float*)malloc(sizeof(float) * (size_t)E);
+        char* taken = (char*)calloc((size_t)E, 1);
+        for (int e = 0; e < E; ++e) {
+            volatile float acc = 0.0f;
+            for (int j = 0; j < d; ++j) {
+                volatile float p = orc_half_to_float(x[(size_t)t * d + j]) * orc_half_to_float(wg[(size_t)e * d + j]);
+                acc = acc + p;
+            }
+            if (bias) acc = acc + bias[e];
+            l[e] = acc;
+        }
+        for (int s = 0; s < k; ++s) {
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || l[e] > l[best]) best = e;
+            }
+            taken[best] = 1;
+            idx[(size_t)t * k + s] = best;
+        }
+        float m = l[idx[(size_t)t * k]];
+        volatile float denom = 0.0f;
+        for (int s = 0; s < k; ++s) denom = denom + expf(l[idx[(size_t)t * k + s]] - m);
+        for (int s = 0; s < k; ++s) gate[(size_t)t * k + s] = expf(l[idx[(size_t)t * k + s]] - m) / denom;
+        free(l);
+        free(taken);
+    }
+    return 0;
+}
+
+/* out[t,:] = fp16_rne( (residual ? residual[t,:] : 0) + sum_s gate[t,s] * y_s ), fp32 throughout, slots in order. */
+int orc_layer_forward_f32(const uint16_t* x, int T, int d, int f, int E, int k, const uint16_t* wg,
+                          const float* bias, const orc_expert* experts, int exact_weights,
+                          const uint16_t* residual, uint16_t* out, int32_t* idx_out, float* gate_out) {
+    if (T < 1 || k > E) return -1;
+    int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)T * k);
+    float* gate = (float*)malloc(sizeof(float) * (size_t)T * k);
+    int rc = orc_route_f32(x, T, d, wg, bias, E, k, idx, gate);
+    if (rc == 0) {
+        for (int p = 0; p < T * k; ++p)
+            if (!experts[idx[p]].resident || !experts[idx[p]].w1.data) rc = -3;
+    }
+    if (rc != 0) { free(idx); free(gate); return rc; }
+    float* ypair = (float*)malloc(sizeof(float) * (size_t)T * k * d);
+    for (int p = 0; p < T * k; ++p) {          /* one (token, slot) pair at a time */
+        const orc_expert* ex = &experts[idx[p]];
+        orc_expert_ffn_f32(ex->prec_int4, &ex->w1, &ex->w3, &ex->w2, x + (size_t)(p / k) * d, 1, d, f,
+                           exact_weights, ypair + (size_t)p * d, NULL);
+    }
+    for (int t = 0; t < T; ++t)
+        for (int c = 0; c < d; ++c) {
+            volatile float acc = 0.0f;
+            for (int s = 0; s < k; ++s) {
+                volatile float p = gate[(size_t)t * k + s] * ypair[((size_t)t * k + s) * d + c];
+                acc = acc + p;
+            }
+            if (residual) acc = orc_half_to_float(residual[(size_t)t * d + c]) + acc;
+            out[(size_t)t * d + c] = orc_float_to_half(acc);
+        }
+    if (idx_out) memcpy(idx_out, idx, sizeof(int32_t) * (size_t)T * k);
+    if (gate_out) memcpy(gate_out, gate, sizeof(float) * (size_t)T * k);
+    free(ypair); free(idx); free(gate);
+    return 0;
+}
+
+/* RMSNorm -> block -> residual in the second mode, in place on h. */
+int orc_chain_layer_f32(uint16_t* h, int T, int d, int f, int E, int k, const uint16_t* rms_gain, float eps,
+                        const uint16_t* wg, const float* bias, const orc_expert* experts, int exact_weights,
+                        int32_t* idx_out, float* gate_out) {
+    uint16_t* n = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * d);
+    uint16_t* out = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * d);
+    for (int t = 0; t < T; ++t) {
+        volatile float ss = 0.0f;
+        for (int j = 0; j < d; ++j) {
+            float v = orc_half_to_float(h[(size_t)t * d + j]);
+            volatile float sq = v * v;
+            ss = ss + sq;
+        }
+        volatile float mean = ss / (float)d;
+        volatile float inv = 1.0f / sqrtf(mean + eps);
+        for (int j = 0; j < d; ++j) {
+            volatile float v = orc_half_to_float(h[(size_t)t * d + j]) * inv;
+            volatile float w = v * orc_half_to_float(rms_gain[j]);
+            n[(size_t)t * d + j] = orc_float_to_half(w);
+        }
+    }
+    int rc = orc_layer_forward_f32(n, T, d, f, E, k, wg, bias, experts, exact_weights, h, out, idx_out, gate_out);
+    if (rc == 0) memcpy(h, out, sizeof(uint16_t) * (size_t)T * d);
+    free(n);
+    free(out);
+    return rc;
+}
+
 /* ---------------------------------------------------------------- threads */
 
 int orc_max_threads(void) {

@@ -62,6 +62,13 @@ def lib():
         L.orc_residual_add.argtypes = [vp, vp, i32, i32]
         L.orc_residual_add.restype = None
         L.orc_chain_layer.argtypes = [vp, i32, i32, i32, i32, i32, vp, f64, vp, vp, ctypes.POINTER(_Expert), vp, vp, vp]
+        L.orc_expert_ffn_f32.argtypes = [i32, ctypes.POINTER(_Mat), ctypes.POINTER(_Mat), ctypes.POINTER(_Mat),
+                                         vp, i32, i32, i32, i32, vp, vp]
+        L.orc_route_f32.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp]
+        L.orc_layer_forward_f32.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, ctypes.POINTER(_Expert), i32, vp, vp,
+                                            vp, vp]
+        L.orc_chain_layer_f32.argtypes = [vp, i32, i32, i32, i32, i32, vp, ctypes.c_float, vp, vp,
+                                          ctypes.POINTER(_Expert), i32, vp, vp]
         L.orc_max_threads.restype = i32
         L.orc_set_threads.argtypes = [i32]
         L.orc_set_threads.restype = None
@@ -202,7 +209,8 @@ def _expert_array(experts: Sequence[Expert]):
 
 
 def _d_ff(experts: Sequence[Expert]) -> int:
-    e = experts[0]
+    """d_ff read off the first expert that is resident (placeholders of absent experts carry no shape)."""
+    e = next((x for x in experts if x.resident), experts[0])
     return e.w2.data.shape[1] * (2 if e.int4 else 1)
 
 
@@ -264,6 +272,82 @@ def chain_layer(h: np.ndarray, rms_gain: np.ndarray, eps: float, wg: np.ndarray,
     if rc != 0:
         raise ValueError("orc_chain_layer: bad arguments")
     return h, idx, gate, normed
+
+
+# ------------------------------------------------------------------ second mode: fp32 accumulators, fp16 intermediates
+
+def expert_ffn_f32(e: Expert, x_rows: np.ndarray, exact_weights: bool = False, want_h: bool = False):
+    """The expert with fp32 accumulators and the hidden row rounded to fp16.  Returns y fp32 [n,d] (and h fp16)."""
+    x_rows = _f16(x_rows)
+    n, d = x_rows.shape
+    f = e.w2.data.shape[1] * (2 if e.int4 else 1)
+    y = np.zeros((n, d), dtype=np.float32)
+    h = np.zeros((n, f), dtype=np.float16) if want_h else None
+    m1, m3, m2 = e.w1.c(), e.w3.c(), e.w2.c()
+    rc = lib().orc_expert_ffn_f32(int(e.int4), ctypes.byref(m1), ctypes.byref(m3), ctypes.byref(m2),
+                                  x_rows.ctypes.data, n, d, f, int(exact_weights), y.ctypes.data, _ptr(h))
+    if rc != 0:
+        raise ValueError("orc_expert_ffn_f32: bad shape")
+    return (y, h) if want_h else y
+
+
+def route_f32(x: np.ndarray, wg: np.ndarray, k: int, bias: Optional[np.ndarray] = None):
+    x, wg = _f16(x), _f16(wg)
+    T, d = x.shape
+    E = wg.shape[0]
+    idx = np.zeros((T, k), dtype=np.int32)
+    gate = np.zeros((T, k), dtype=np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    rc = lib().orc_route_f32(x.ctypes.data, T, d, wg.ctypes.data, _ptr(bias), E, k, idx.ctypes.data, gate.ctypes.data)
+    if rc != 0:
+        raise ValueError("orc_route_f32: bad arguments")
+    return idx, gate
+
+
+def layer_forward_f32(x: np.ndarray, wg: np.ndarray, experts: Sequence[Expert], k: int,
+                      bias: Optional[np.ndarray] = None, exact_weights: bool = False,
+                      residual: Optional[np.ndarray] = None):
+    """The block in the second mode.  Returns (out fp16 [T,d], idx, gate)."""
+    x, wg = _f16(x), _f16(wg)
+    T, d = x.shape
+    out = np.zeros((T, d), dtype=np.float16)
+    idx = np.zeros((T, k), dtype=np.int32)
+    gate = np.zeros((T, k), dtype=np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    if residual is not None:
+        residual = _f16(residual)
+    arr = _expert_array(experts)
+    rc = lib().orc_layer_forward_f32(x.ctypes.data, T, d, _d_ff(experts), len(experts), k, wg.ctypes.data, _ptr(bias),
+                                     arr, int(exact_weights), _ptr(residual), out.ctypes.data, idx.ctypes.data,
+                                     gate.ctypes.data)
+    if rc == -3:
+        raise LookupError("a routed expert is not resident")
+    if rc != 0:
+        raise ValueError("orc_layer_forward_f32: bad arguments")
+    return out, idx, gate
+
+
+def chain_layer_f32(h: np.ndarray, rms_gain: np.ndarray, eps: float, wg: np.ndarray, experts: Sequence[Expert], k: int,
+                    bias: Optional[np.ndarray] = None, exact_weights: bool = False):
+    """One (RMSNorm -> block -> residual) step in the second mode.  Returns (h_new fp16, idx, gate)."""
+    h = _f16(h).copy()
+    rms_gain, wg = _f16(rms_gain), _f16(wg)
+    T, d = h.shape
+    idx = np.zeros((T, k), dtype=np.int32)
+    gate = np.zeros((T, k), dtype=np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    arr = _expert_array(experts)
+    rc = lib().orc_chain_layer_f32(h.ctypes.data, T, d, _d_ff(experts), len(experts), k, rms_gain.ctypes.data, eps,
+                                   wg.ctypes.data, _ptr(bias), arr, int(exact_weights), idx.ctypes.data,
+                                   gate.ctypes.data)
+    if rc == -3:
+        raise LookupError("a routed expert is not resident")
+    if rc != 0:
+        raise ValueError("orc_chain_layer_f32: bad arguments")
+    return h, idx, gate
 
 
 def max_threads() -> int:
