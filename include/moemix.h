@@ -28,6 +28,11 @@
  *     consecutive columns of one row share an fp16 scale and an fp16 zero,
  *     two codes per byte, the even column in the low nibble;
  *     dequantized weight = fp16_rne( fp32(code) * fp32(scale) + fp32(zero) ).
+ *     moe_dequant_int4 and the kernels for shapes outside the tiled paths produce exactly these bits.  The
+ *     tiled matrix kernels evaluate the same expression inside their products without materialising the
+ *     weight: the multi-token kernels with one fp16 multiply-add (a single rounding), the one-token kernels
+ *     in the factored form scale * sum(code * x) + zero * sum(x) in fp32 (no rounding of the weight); both
+ *     stay within the tolerance stated for the block outputs, not bit-exact per weight.
  *   - d_model and d_ff must be multiples of 64, d_model <= 8192, d_ff <= 16384 (else MOE_ESHAPE);
  *     n_experts <= MOE_MAX_EXPERTS; 1 <= top_k <= min(n_experts, MOE_MAX_TOPK).
  */
@@ -117,6 +122,8 @@ int moe_permute(const moe_layer* layer, const int32_t* topk_idx, int T, int32_t*
  * x_rows: device fp16 [n, d_model]; y: device fp32 [n, d_model] (overwritten).
  * ws: at least moe_workspace_bytes(layer, ceil(n / top_k)) bytes (the hidden rows live there).
  * Fails with MOE_ENOTRESIDENT on the host if the expert is not resident.
+ * n == 1 runs the same one-token kernels as moe_layer_forward with T == 1 (when the shape is one they
+ * take), n > 1 the multi-token kernels, so each can be checked alone, before gating and weighted average.
  */
 int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows, int n, float* y, void* ws,
                          size_t ws_bytes, moe_stream_t stream);
@@ -220,8 +227,17 @@ enum { MOE_KERNEL_ROUTE = 0,   /* gating (with the RMSNorm of the chained config
        MOE_KERNEL_PERMUTE = 1, /* grouping */
        MOE_KERNEL_UP = 2,      /* up-projection + SiLU gate */
        MOE_KERNEL_DOWN = 3,    /* down-projection (with the weighted average at one token) */
-       MOE_KERNEL_COMBINE = 4  /* weighted average of a multi-token call */ };
+       MOE_KERNEL_COMBINE = 4, /* weighted average of a multi-token call */
+       MOE_KERNEL_STREAM_READ = 5 /* the plain read of moe_stream_read */ };
 int moe_trace_kernel(int kernel, void* start_event, void* stop_event);
+
+/*
+ * Measurement hook: one kernel that reads `bytes` (multiple of 16) of device memory at `src` (16-byte aligned)
+ * once, with the same streamed 128-bit loads as the expert kernels and no arithmetic.  Timed by the caller, it
+ * gives the streaming-read ceiling of the GPU at a given size, beside which the bandwidth-bound kernels are
+ * reported.  sink: device, 4 bytes, practically never written.
+ */
+int moe_stream_read(const void* src, size_t bytes, void* sink, moe_stream_t stream);
 
 /*
  * Partitioner / planner (§3, Eq. 1): host-only arithmetic, no device work.  From the GPU memory available and the

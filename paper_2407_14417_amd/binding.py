@@ -24,6 +24,7 @@ EXPORTS = (
     "moe_workspace_bytes", "moe_route", "moe_permute", "moe_expert_ffn_mixed", "moe_layer_forward",
     "moe_chain_forward", "moe_dequant_int4", "moe_quantize_int4", "moe_synth_fill_f16", "moe_read_status",
     "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan", "moe_swap_slot_bytes", "moe_layer_forward_swap",
+    "moe_stream_read",
 )
 
 
@@ -98,6 +99,7 @@ def lib():
         L.moe_swap_slot_bytes.restype = sz
         L.moe_layer_forward_swap.argtypes = [LP, ctypes.POINTER(CSwap), vp, i32, vp, vp, vp, vp, sz, vp,
                                              ctypes.POINTER(ctypes.c_int32)]
+        L.moe_stream_read.argtypes = [vp, sz, vp, vp]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_version.restype = i32
         for name in EXPORTS:
@@ -265,11 +267,15 @@ def moe_read_status(ws) -> int:
     return v.value
 
 
-KERNEL_ROUTE, KERNEL_PERMUTE, KERNEL_UP, KERNEL_DOWN, KERNEL_COMBINE = range(5)
+KERNEL_ROUTE, KERNEL_PERMUTE, KERNEL_UP, KERNEL_DOWN, KERNEL_COMBINE, KERNEL_STREAM_READ = range(6)
 
 
 def moe_trace_kernel(kernel: int, start_event: int, stop_event: int) -> None:
     _check(lib().moe_trace_kernel(kernel, start_event, stop_event))
+
+
+def moe_stream_read(src, nbytes: int, sink) -> None:
+    _check(lib().moe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()))
 
 
 def moe_plan(mem_gpu: int, size_non_expert: int, size_e16: int, size_e4: int, num_experts: int, preference: int,

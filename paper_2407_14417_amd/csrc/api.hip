@@ -51,45 +51,15 @@ int check_layer(const moe_layer* L) {
     return MOE_OK;
 }
 
-// Launch shapes that can be overridden from the environment for measurement sweeps.
-struct Tuning {
-    int up_blocks;   // MOEMIX_UP_BLOCKS: workgroups of the batch-1 up-projection
-    bool no_mfma;    // MOEMIX_NO_MFMA=1: multi-row calls take the shape-agnostic kernels (A/B timing)
-    int mfma_ct;     // MOEMIX_MFMA_CT: 16-row activation tiles per chunk (1, 2, 4, 8), 0 = planned from the shape
-    int mfma_splits; // MOEMIX_MFMA_SPLITS: contraction splits of the down-projection, 0 = planned
-};
-const Tuning& tuning() {
-    static const Tuning t = [] {
-        Tuning v{1024, false, 0, 0};
-        if (const char* s = getenv("MOEMIX_UP_BLOCKS")) {
-            const int n = atoi(s);
-            if (n >= 1 && n <= 65536) v.up_blocks = n;
-        }
-        if (const char* s = getenv("MOEMIX_NO_MFMA")) v.no_mfma = atoi(s) != 0;
-        if (const char* s = getenv("MOEMIX_MFMA_CT")) {
-            const int n = atoi(s);
-            if (n == 1 || n == 2 || n == 4 || n == 8) v.mfma_ct = n;
-        }
-        if (const char* s = getenv("MOEMIX_MFMA_SPLITS")) {
-            const int n = atoi(s);
-            if (n >= 1 && n <= 16) v.mfma_splits = n;
-        }
-        return v;
-    }();
-    return t;
-}
+// Workgroups of the batch-1 up-projection: four per compute unit, each wavefront taking an equal share of the
+// routed experts' stored bytes.
+constexpr int kDecodeUpBlocks = 1024;
 
 // Which kernels serve T tokens of a block: T == 1 the batch-1 kernels, otherwise the matrix-core path when
 // the shape allows it, else the shape-agnostic kernels.
-bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff) && !tuning().no_mfma; }
+bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff); }
 
-MfmaPlan plan_for(const moe_layer* L, int rows) {
-    MfmaPlan p = plan_mfma(rows, L->d_model, L->d_ff, L->n_experts);
-    if (tuning().mfma_ct) p.ct = tuning().mfma_ct;
-    if (tuning().mfma_splits && (L->d_ff / 128) % tuning().mfma_splits == 0 && (L->d_ff / 128) / tuning().mfma_splits >= 2)
-        p.down_splits = tuning().mfma_splits;
-    return p;
-}
+MfmaPlan plan_for(const moe_layer* L, int rows) { return plan_mfma(rows, L->d_model, L->d_ff, L->n_experts); }
 
 int y_splits_for(const moe_layer* L, int T) {
     if (!use_mfma(L, T * L->top_k)) return 1;
@@ -134,7 +104,7 @@ int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int
     if (rms_gain) x = w.xn;
     if (T == 1 && decode_shape_ok(d, f)) {
         // batch-1 decode: no grouping needed, the weighted average is fused into the down-projection
-        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, tuning().up_blocks, st);
+        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, kDecodeUpBlocks, st);
         launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, residual, out, w.status, st);
         return check_hip(st);
     }
@@ -234,9 +204,13 @@ int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows,
     RowMap rows{nullptr, nullptr, layer->top_k, expert, n};
     const int d = layer->d_model, f = layer->d_ff;
     launch_zero_words(w.status, 1, st);   // the status word describes this call
-    if (use_mfma(layer, n)) {
+    if (n == 1 && decode_shape_ok(d, f)) {
+        // one row: the batch-1 kernels, with the routing result "this expert, weight 1" written to the workspace
+        launch_single_route(w.idx, w.gate, expert, st);
+        launch_decode_up(table, w.idx, (const half_t*)x_rows, d, f, 1, w.h, w.status, kDecodeUpBlocks, st);
+        launch_decode_down(table, w.idx, w.gate, w.h, d, f, 1, nullptr, nullptr, w.status, st, y);
+    } else if (use_mfma(layer, n)) {
         MfmaPlan p = plan_mfma(n, d, f, 1);       // all n rows belong to the one expert
-        if (tuning().mfma_ct) p.ct = tuning().mfma_ct;
         launch_ffn_up_mfma(table, layer->n_experts, rows, n, (const half_t*)x_rows, d, f, w.h, p.ct, w.status, st);
         // few rows: the contraction of the down-projection is split over as many workgroups as the workspace's
         // partial-result region was sized for, and the partials are added in order
@@ -309,7 +283,7 @@ void run_experts(const moe_layer* L, const DevExperts& table, const half_t* x, i
                  const half_t* decode_residual, half_t* out, hipStream_t st) {
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
     if (T == 1 && decode_shape_ok(d, f)) {
-        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, tuning().up_blocks, st);
+        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, kDecodeUpBlocks, st);
         launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, decode_residual, out, w.status, st);
         return;
     }
@@ -470,6 +444,13 @@ int moe_synth_fill_f16(void* dst, size_t n, size_t first, uint64_t seed, uint64_
     if (!dst && n) return fail(MOE_EINVAL, "moe_synth_fill_f16: NULL destination");
     if (kind != 0 && kind != 1) return fail(MOE_EINVAL, "moe_synth_fill_f16: kind=%d", kind);
     launch_synth_fill((half_t*)dst, n, first, seed, stream_id, scale, kind, (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_stream_read(const void* src, size_t bytes, void* sink, moe_stream_t stream) {
+    if (!src || !sink) return fail(MOE_EINVAL, "moe_stream_read: NULL argument");
+    if (bytes % 16 || (uintptr_t)src % 16) return fail(MOE_EINVAL, "moe_stream_read: bytes and src must be multiples of 16");
+    if (bytes) launch_stream_read(src, bytes, (uint32_t*)sink, 512, (hipStream_t)stream);
     return check_hip((hipStream_t)stream);
 }
 

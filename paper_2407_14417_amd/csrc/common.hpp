@@ -114,6 +114,16 @@ __device__ __forceinline__ float wave_total(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// Lanes of one wavefront hand data to each other through a wavefront-private LDS region without a workgroup
+// barrier.  This orders the wavefront's LDS writes before its later reads of what other lanes wrote (the hardware
+// keeps one wavefront's LDS accesses in program order; the fences keep the compiler from reordering them and
+// cost no instruction).
+__device__ __forceinline__ void wave_lds_handover() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Reinterpret a 32-bit word as two halves.  The argument is taken by value on purpose: the bit-cast
 // builtin applied directly to an element of a vector lvalue (v[j]) reads element 0 whatever j is.
 __device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }

@@ -124,13 +124,8 @@ __device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readf
 // Rows of all routed slots are laid end to end, weighted by their stored bytes (9 units per 4-bit row
 // pair, 32 per 16-bit one), and cut into equal shares, one per wavefront: every wavefront streams the
 // same number of bytes whatever the precision mix.
-#ifndef MOEMIX_UP_BUFS
-#define MOEMIX_UP_BUFS 2
-#endif
-#ifndef MOEMIX_UP_RB
-#define MOEMIX_UP_RB 2
-#endif
-constexpr int kUpRowsI4 = MOEMIX_UP_RB;         // rows per register buffer of the 4-bit path
+constexpr int kUpRowsI4 = 2;                    // rows per register buffer of the 4-bit path
+constexpr int kUpBufsI4 = 2;                    // register buffers in the ring of the 4-bit path
 constexpr uint32_t kMinUnitsPerWave = 100;      // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short
 
 template <int NCH>   // d_model / 2048
@@ -200,8 +195,10 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                 for (int a = 0; a < 4; ++a) sg[a] = load_stream(at(szm[a], off));
             };
             auto publish_group = [&]() {
+                wave_lds_handover();   // the previous run has been read by every lane
 #pragma unroll
                 for (int a = 0; a < 4; ++a) *(uint4_t*)(my_lds + a * 1024 + lane * 16) = sg[a];
+                wave_lds_handover();
             };
             struct Rows {
                 uint4_t pk1[RB][NCH], pk3[RB][NCH];
@@ -246,7 +243,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
             };
             // a ring of NB register buffers: NB - 1 sets of rows are in flight while one is used (a set of 4-bit
             // rows is used up in well under a microsecond, less than a trip to device memory under load)
-            constexpr int NB = MOEMIX_UP_BUFS;
+            constexpr int NB = kUpBufsI4;
             Rows buf[NB];
 #pragma unroll
             for (int j = 0; j < NB - 1; ++j)
@@ -332,7 +329,8 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
                                                            const float* __restrict__ gate,
                                                            const half_t* __restrict__ h, int d, int f, int k,
                                                            const half_t* __restrict__ residual,
-                                                           half_t* __restrict__ out, int32_t* status) {
+                                                           half_t* __restrict__ out, float* __restrict__ out32,
+                                                           int32_t* status) {
     __shared__ float part[8][kDownRows];
     const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
     const uint32_t wave = wave_index();
@@ -443,8 +441,15 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
         float t = residual ? (float)residual[row] : 0.0f;
         float sum = 0.0f;
         for (int w = 0; w < n_waves; ++w) sum += part[w][threadIdx.x];
-        out[row] = (half_t)(t + sum);
+        if (out32) out32[row] = t + sum;      // one expert alone: the unrounded result
+        else out[row] = (half_t)(t + sum);
     }
+}
+
+// Routing result "this one expert with weight 1", for a single expert run through the batch-1 kernels.
+__global__ void single_route_kernel(int32_t* idx, float* gate, int expert) {
+    idx[0] = expert;
+    gate[0] = 1.0f;
 }
 
 }  // namespace
@@ -463,9 +468,13 @@ void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x,
 }
 
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
-                        int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st) {
+                        int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st, float* out32) {
     TraceScope trace(kKernelDown, st);
-    decode_down_kernel<<<d / kDownRows, (f / 2048) * 64, 0, st>>>(ex, idx, gate, h, d, f, k, residual, out, status);
+    decode_down_kernel<<<d / kDownRows, (f / 2048) * 64, 0, st>>>(ex, idx, gate, h, d, f, k, residual, out, out32, status);
+}
+
+void launch_single_route(int32_t* idx, float* gate, int expert, hipStream_t st) {
+    single_route_kernel<<<1, 1, 0, st>>>(idx, gate, expert);
 }
 
 }  // namespace moemix

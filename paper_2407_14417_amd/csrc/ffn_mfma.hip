@@ -24,22 +24,12 @@ namespace moemix {
 namespace {
 
 // Weights of launches with few activation rows per expert are read once, in whole lines: streamed past the caches'
-// replacement order.  MOEMIX_TEMPORAL_NA: operand count per wavefront from which on lines are kept for sibling chunks;
-// MOEMIX_DIRECT_NCT: activation tiles per chunk from which on 16-bit weights go straight to registers.
-#define MOEMIX_CLOAD(p) __builtin_nontemporal_load(p)
-#ifndef MOEMIX_TEMPORAL_NA
-#define MOEMIX_TEMPORAL_NA 4
-#endif
-#ifndef MOEMIX_DIRECT_NCT
-#define MOEMIX_DIRECT_NCT 8
-#endif
-#ifndef MOEMIX_NA_SMALL
-#define MOEMIX_NA_SMALL 2
-#endif
-#ifndef MOEMIX_SPB_MAX
-#define MOEMIX_SPB_MAX 2
-#endif
-#define MOEMIX_SPB(ct) ((8 / (ct)) < MOEMIX_SPB_MAX ? (8 / (ct)) : MOEMIX_SPB_MAX)
+// replacement order.
+constexpr int kTemporalNA = 4;     // A operands per wavefront from which on weight lines are kept for sibling chunks
+constexpr int kDirectNCT = 8;      // activation tiles per chunk from which on 16-bit weights go straight to registers
+constexpr int kNASmall = 2;        // A operands per wavefront of launches with at most 32 rows per chunk
+constexpr int kSPBMax = 2;         // most 128-column steps per LDS stage
+constexpr int spb_for(int ct) { return (8 / ct) < kSPBMax ? (8 / ct) : kSPBMax; }
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
 
 struct MfmaArgs {
@@ -255,10 +245,11 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     // launches with many activation rows per expert run several chunks of one expert side by side on
                     // the same XCD: the second reader of a weight line should find it in L2, so the line is not
                     // marked as used once there
-                    stg[t][hb * UL + q] = NA >= MOEMIX_TEMPORAL_NA ? *src : MOEMIX_CLOAD(src);
+                    stg[t][hb * UL + q] = NA >= kTemporalNA ? *src : __builtin_nontemporal_load(src);
                 }
     };
     auto stage_to_lds = [&]() {
+        wave_lds_handover();   // the previous unit has been read by every lane
 #pragma unroll
         for (int t = 0; t < NA; ++t)
 #pragma unroll
@@ -266,6 +257,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
                 for (int q = 0; q < UL; ++q)
                     *(uint4_t*)(wreg + t * (16 * UB) + hb * (8 * UB) + q * 128 + w_wr) = stg[t][hb * UL + q];
+        wave_lds_handover();
     };
     auto lds_to_operands = [&](int unit) {
         // (4-bit: for the moved-back last pair of an odd range the wanted step sits in the second half)
@@ -284,7 +276,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     // stream, so the A operands skip LDS: lane (r16, c4) loads its 8 weights of every 32-column sub-step
     // straight from device memory (16 rows x 64 bytes per instruction), one step ahead, into the other half of a
     // two-step register ring.
-    constexpr bool DIRECT = !INT4 && NCT >= MOEMIX_DIRECT_NCT;
+    constexpr bool DIRECT = !INT4 && NCT >= kDirectNCT;
     uint4_t ad[DIRECT ? 2 : 1][NA][4];
     uint32_t doff[NA];
 #pragma unroll
@@ -426,9 +418,9 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 template <bool UP, int CT>
 __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     constexpr int MC = 16 * CT;                  // activation rows per chunk
-    constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;   // A operands per wavefront
+    constexpr int NA = CT <= 2 ? kNASmall : 4;   // A operands per wavefront
     constexpr int NT = UP ? 32 * NA : 64 * NA;   // weight rows per workgroup
-    constexpr int SPB = MOEMIX_SPB(CT);          // 128-column steps per LDS stage
+    constexpr int SPB = spb_for(CT);          // 128-column steps per LDS stage
     extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][SPB * 256 + 16]
     const int tid = threadIdx.x;
 
@@ -493,10 +485,10 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
 
 template <bool UP, int CT>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
-    constexpr int NA = CT <= 2 ? MOEMIX_NA_SMALL : 4;
+    constexpr int NA = CT <= 2 ? kNASmall : 4;
     // activation stages + 4 wavefronts x NA operands of weight staging
-    const size_t lds_max = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * 4096;
-    const size_t lds_bytes = 2u * 16 * CT * (MOEMIX_SPB(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
+    const size_t lds_max = 2u * 16 * CT * (spb_for(CT) * kKTile * 2 + 16) + 4 * NA * 4096;
+    const size_t lds_bytes = 2u * 16 * CT * (spb_for(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
     // the attribute belongs to (kernel, device): set it once per device of the process (bit d of the mask; devices
     // past the 64th set it on every launch)
     static std::atomic<unsigned long long> configured{0};
@@ -548,7 +540,7 @@ MfmaPlan plan_mfma(int P, int d, int f, int E) {
     p.ct = avg <= 16 ? 1 : avg <= 32 ? 2 : avg <= 64 ? 4 : 8;
     // down-projection: split the contraction until there are enough workgroups for 256 compute units
     const int steps = f / kKTile;
-    const int down_rows = 64 * (p.ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    const int down_rows = 64 * (p.ct <= 2 ? kNASmall : 4);
     const int base = ((d + down_rows - 1) / down_rows) * (P / (16 * p.ct) + 1);
     int best = 1;
     for (int s = 1; s <= 16; ++s)
@@ -565,7 +557,7 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
-    const int up_rows = 32 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    const int up_rows = 32 * (ct <= 2 ? kNASmall : 4);
     dim3 grid((f + up_rows - 1) / up_rows, chunk_slots(rows, P, E, ct), 1);
     launch_ct<true>(a, ct, grid, st);
 }
@@ -579,7 +571,7 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
     a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
-    const int down_rows = 64 * (ct <= 2 ? MOEMIX_NA_SMALL : 4);
+    const int down_rows = 64 * (ct <= 2 ? kNASmall : 4);
     dim3 grid((d + down_rows - 1) / down_rows, chunk_slots(rows, P, E, ct), splits);
     launch_ct<false>(a, ct, grid, st);
 }

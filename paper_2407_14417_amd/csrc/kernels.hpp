@@ -49,8 +49,12 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
 bool decode_shape_ok(int d, int f);
 void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
                       int32_t* status, int blocks, hipStream_t st);
+// out32 != null: the result is written there unrounded (fp32) instead of to `out`.
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
-                        int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st);
+                        int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st,
+                        float* out32 = nullptr);
+// idx[0] = expert, gate[0] = 1: one expert alone through the batch-1 kernels.
+void launch_single_route(int32_t* idx, float* gate, int expert, hipStream_t st);
 
 // out[t, :] = fp16( (residual ? residual[t, :] : 0) + sum_s gate[t, s] * sum_p y[p][inv[t*k + s], :] ),
 // p over the `splits` partial results, `split_stride` elements apart.
@@ -63,6 +67,8 @@ void launch_zero_words(int32_t* p, int n, hipStream_t st);
 void launch_dequant_int4(const DevMat& m, int out, int in, half_t* w, hipStream_t st);
 void launch_quantize_int4(const half_t* w, int out, int in, uint8_t* packed, half_t* scale, half_t* zero,
                           hipStream_t st);
+// Reads `bytes` (a multiple of 16) of device memory once with streamed 128-bit loads.
+void launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t st);
 void launch_synth_fill(half_t* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale, int kind,
                        hipStream_t st);
 
@@ -72,7 +78,7 @@ namespace moemix {
 
 // Kernel ids for moe_trace_kernel (same values as MOE_KERNEL_* in the public header).
 enum KernelId { kKernelRoute = 0, kKernelPermute = 1, kKernelUp = 2, kKernelDown = 3, kKernelCombine = 4,
-                kKernelCount = 5 };
+                kKernelStreamRead = 5, kKernelCount = 6 };
 
 // One-shot event bracket around the next launch of a given kernel on this thread.
 void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop);

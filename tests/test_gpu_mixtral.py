@@ -2,6 +2,8 @@
 configurations the benchmark times.  Device weights come from the library's seeded fill and device
 quantizer; the oracle side regenerates the same tensors with the host generator and its own quantizer,
 so these tests also cover fill and quantizer at full size."""
+from pathlib import Path
+
 import numpy as np
 import pytest
 
@@ -78,6 +80,22 @@ def test_decode_batch1_all_three_precision_pairs(orc, decode_layer):
         assert_ffn_close(out.cpu().numpy(), ref, f"decode kind={kind}")
 
 
+def test_decode_expert_alone_both_precisions(orc, decode_layer):
+    """moe_expert_ffn_mixed with one row at the Mixtral shape runs the batch-1 GEMV kernels by themselves
+    (no gating, weight 1): a 16-bit expert and a 4-bit one, unrounded fp32 result against the oracle."""
+    cfg = DECODE
+    ws = mm.alloc_workspace(decode_layer, 1)
+    x = synth.normal_f16((1, cfg.d), 1.0, cfg.seed, synth.x_stream(7))
+    for e in (1, 6):
+        _say(f"decode GEMV alone, expert {e} ({'4-bit' if e in cfg.int4_experts else '16-bit'})")
+        y = torch.full((1, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+        mm.moe_expert_ffn_mixed(decode_layer, e, dev(x), y, ws)
+        assert mm.moe_read_status(ws) == 0
+        ex = _host_expert(orc, cfg, e)
+        assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(ex, x), f"decode expert {e} alone")
+        del ex
+
+
 def test_decode_device_weights_equal_host_weights(orc, decode_layer):
     """Device fill + device quantizer reproduce the host generator + oracle quantizer at full size (one expert each)."""
     for e in (0, 4):
@@ -111,9 +129,10 @@ def test_batched_decode_all_int4(orc):
     assert_ffn_close(out.cpu().numpy(), ref, "batched")
 
 
-def test_prefill_skewed_sampled_tokens(orc):
-    """T=512 on the device; routing checked for every token, outputs for a seeded sample of 48 tokens that
-    covers every expert (the oracle evaluates those one by one)."""
+def test_prefill_skewed_all_tokens(orc):
+    """T=512 on the device; routing and outputs checked for every one of the 512 tokens, so every 16-row tile of
+    every 128-row chunk of every expert (full chunks, ragged last chunks and their ragged last tiles) is compared.
+    The oracle evaluates each expert on all the rows routed to it."""
     cfg = PREFILL
     layer = workload.device_layer(cfg.d, cfg.f, cfg.E, cfg.k, cfg.int4_experts, seed=cfg.seed, zipf=cfg.zipf)
     wg, bias = common.gate_matrix(cfg), common.gate_bias(cfg)
@@ -131,16 +150,14 @@ def test_prefill_skewed_sampled_tokens(orc):
     counts = np.bincount(ref_idx.reshape(-1), minlength=cfg.E)
     _say(f"expert loads {counts.tolist()}")
     assert counts[0] > 3 * counts[-1]                                  # the skew is there
-    rng = np.random.default_rng(0)
-    sample = set(rng.choice(cfg.T, 40, replace=False).tolist())
-    for e in range(cfg.E):                                             # make sure every expert is covered
-        sample.add(int(np.argwhere((ref_idx == e).any(axis=1))[0, 0]))
-    sample = sorted(sample)
-    ref = _oracle_tokens(orc, cfg, x, wg, bias, ref_idx, ref_gate, sample)
-    assert_ffn_close(out.cpu().numpy()[sample], ref, "prefill sample")
-    # properties that hold for every token: finite, and zero rows only for zero input
-    o = out.cpu().numpy().astype(np.float64)
-    assert np.isfinite(o).all() and (np.abs(o).max(axis=1) > 0).all()
+    assert counts.max() > 256 and (counts % 16 != 0).any()             # several chunks per expert, ragged tiles
+    ref = _oracle_tokens(orc, cfg, x, wg, bias, ref_idx, ref_gate, list(range(cfg.T)))
+    got = out.cpu().numpy()
+    mf, l2 = assert_ffn_close(got, ref, "prefill, all tokens")
+    _say(f"prefill all 512 tokens: max|err|/max|ref|={mf:.3e} relL2={l2:.3e}")
+    # and per token, so that one bad row cannot hide in the norm of 512
+    err = np.abs(got.astype(np.float64) - ref).max(axis=1)
+    assert (err <= common.MAX_ERR_FRAC * np.abs(ref).max(axis=1)).all()
 
 
 def _graph_replays_equal_eager(layer, x_steps, T, k, d, replays=3):
@@ -203,7 +220,7 @@ def test_decode_graph_replay_equals_eager_and_oracle(orc, decode_layer):
 
 def test_batched_graph_replay_equals_eager(orc):
     """16 tokens, all experts 4-bit (matrix-core path: grouping, split down-projection, weighted average) in one
-    HIP graph, replayed; one step is checked against the oracle on a sample of tokens."""
+    HIP graph, replayed; one step is checked against the oracle on all of its tokens."""
     cfg = BATCHED
     layer = workload.device_layer(cfg.d, cfg.f, cfg.E, cfg.k, cfg.int4_experts, seed=cfg.seed, router="uniform")
     wg = common.gate_matrix(cfg)
@@ -213,17 +230,41 @@ def test_batched_graph_replay_equals_eager(orc):
     x = steps[1]
     ref_idx, ref_gate = orc.route(x, wg, cfg.k)
     assert np.array_equal(idx_e[1].cpu().numpy(), ref_idx)
-    sample = [0, 7, 15]
-    ref = _oracle_tokens(orc, cfg, x, wg, None, ref_idx, ref_gate, sample)
-    assert_ffn_close(out_e[1].cpu().numpy()[sample], ref, "batched graph step 1 sample")
+    ref = _oracle_tokens(orc, cfg, x, wg, None, ref_idx, ref_gate, list(range(cfg.T)))
+    assert_ffn_close(out_e[1].cpu().numpy(), ref, "batched graph step 1, all 16 tokens")
+
+
+def _chain_golden():
+    """tests/golden/chain_fp32_mode_deviation.txt: the accepted seed and, per layer, what the CPU experiment measured
+    (written by tests/golden/make_chain_deviation.py from the oracle alone)."""
+    path = Path(__file__).resolve().parent / "golden" / "chain_fp32_mode_deviation.txt"
+    seed, gap_threshold, cols, rows = None, None, None, []
+    for line in path.read_text().splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        if line.startswith("seed ="):
+            seed = int(line.split("=")[1])
+        elif line.startswith("gap_threshold ="):
+            gap_threshold = float(line.split("=")[1])
+        elif line.startswith("layer "):
+            cols = line.split()
+        else:
+            rows.append(dict(zip(cols, [float(v) for v in line.split()])))
+    return seed, gap_threshold, rows
 
 
 def test_chain_32_layers_decode(orc):
     """32 x (RMSNorm -> MoE -> residual), T=1, 256 experts of which a seeded random half is 4-bit (57.8 GB
-    resident).  The oracle regenerates only the routed experts.  Teacher-forced per layer; the free-running
-    trajectory is compared up to the first layer whose top-3 logit gap is below 1e-2."""
+    resident).  The oracle regenerates only the routed experts.
+    Teacher-forced: every block, fed the oracle's input of its layer, meets the plain block tolerance (both
+    criteria) and takes the oracle's routing decision.
+    Free-running: the seed is the one whose oracle trajectory keeps every top-3 router gap >= 1e-2 (asserted
+    here again), so routing must agree at every layer; the final hidden state may deviate from the double oracle's
+    by at most twice what the oracle's own fp32-accumulator mode deviates on the same 32 layers (recorded in
+    tests/golden/ by a CPU-only script)."""
     d, f, E, k, L, eps = 4096, 14336, 8, 2, 32, 1e-5
-    seed = 1          # first seed whose oracle trajectory keeps every top-3 logit gap above 1e-2 (found on the CPU)
+    seed, gap_threshold, golden = _chain_golden()
+    assert len(golden) == L
     mask = synth.precision_mask(E * L, E * L // 2, seed)
     layers, host_cfgs = [], []
     for l in range(L):
@@ -236,50 +277,64 @@ def test_chain_32_layers_decode(orc):
     gains = [dev(g) for _ in range(L)]
     h0 = synth.normal_f16((1, d), 1.0, seed, synth.x_stream(0))
     ws = mm.alloc_workspace(layers[0], 1)
-    # free-running device trajectory
+    # free-running device trajectory: the whole chain in one call ...
     h = dev(h0)
     idx_all = torch.empty((L, 1, k), dtype=torch.int32, device="cuda")
     mm.moe_chain_forward(mm.Chain(layers, gains), eps, h, ws, idx_all)
     assert mm.moe_read_status(ws) == 0
     idx_all = idx_all.cpu().numpy()
     h_dev = h.cpu().numpy()
+    # ... and layer by layer (same kernels, same bits), to see the hidden state after every layer
+    h_step = dev(h0)
+    h_dev_layers = []
+    for l in range(L):
+        mm.moe_chain_forward(mm.Chain([layers[l]], [gains[l]]), eps, h_step, ws, None)
+        h_dev_layers.append(h_step.cpu().numpy())
+    assert np.array_equal(h_dev_layers[-1].view(np.uint16), h_dev.view(np.uint16))
     # oracle trajectory, layer by layer, building only the two routed experts of each layer
     hs = [h0]
-    first_unsafe = None
+    report = ["layer gap n_int4 tf_block_max tf_block_l2 free_max free_l2 fp32_mode_free_max fp32_mode_free_l2"]
     for l in range(L):
         cfg = host_cfgs[l]
         wg = common.gate_matrix(cfg)
         normed = orc.rmsnorm(hs[-1], g, eps)
         lg = np.sort(common.logits_f64(normed, wg, None)[0])[::-1]
         gap = min(lg[0] - lg[1], lg[1] - lg[2])
+        assert gap >= gap_threshold, f"layer {l}: top-3 gap {gap:.3e}: the stored seed is not the safe one"
+        assert abs(gap - golden[l]["gap"]) < 1e-5
         ref_idx, ref_gate = orc.route(normed, wg, k)
+        assert list(ref_idx[0]) == [int(golden[l]["idx0"]), int(golden[l]["idx1"])]
         out = _oracle_tokens(orc, cfg, normed, wg, None, ref_idx, ref_gate, [0])
         hs.append(orc.residual_add(hs[-1], out))
-        if first_unsafe is None and gap < 1e-2:
-            first_unsafe = l
-        # teacher-forced device layer on the oracle's input
+        # teacher-forced: the block alone on the oracle's normed input, both criteria of the block tolerance
+        blk = torch.empty((1, d), dtype=torch.float16, device="cuda")
+        idx_t = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        mm.moe_layer_forward(layers[l], dev(normed), blk, ws, idx_t, None)
+        assert np.array_equal(idx_t.cpu().numpy(), ref_idx), f"teacher-forced layer {l}"
+        tf_max, tf_l2 = assert_ffn_close(blk.cpu().numpy(), out, f"teacher-forced block {l}")
+        # extra: the fused RMSNorm + block + residual step on the oracle's hidden state (the stored state is rounded
+        # to fp16 on both sides, which can move an element by one unit in its last place)
         ht = dev(hs[l])
-        idx_t = torch.empty((1, 1, k), dtype=torch.int32, device="cuda")
-        mm.moe_chain_forward(mm.Chain([layers[l]], [gains[l]]), eps, ht, ws, idx_t)
-        if gap >= 1e-3:
-            assert np.array_equal(idx_t.cpu().numpy()[0], ref_idx), f"layer {l}"
-            upd = ht.cpu().numpy().astype(np.float64) - hs[l].astype(np.float64)
-            ref = hs[l + 1].astype(np.float64) - hs[l].astype(np.float64)
-            ulp = 2.0 ** -10 * np.abs(hs[l + 1].astype(np.float64)).max()
-            assert np.abs(upd - ref).max() <= 1e-2 * np.abs(ref).max() + ulp, f"layer {l}"
-        if first_unsafe is None:
-            assert np.array_equal(idx_all[l], ref_idx), f"free-running layer {l}"
+        mm.moe_chain_forward(mm.Chain([layers[l]], [gains[l]]), eps, ht, ws, idx_t.reshape(1, 1, k))
+        assert np.array_equal(idx_t.cpu().numpy(), ref_idx), f"fused step, layer {l}"
+        upd = ht.cpu().numpy().astype(np.float64) - hs[l].astype(np.float64)
+        ref = hs[l + 1].astype(np.float64) - hs[l].astype(np.float64)
+        ulp = 2.0 ** -10 * np.abs(hs[l + 1].astype(np.float64)).max()
+        assert np.abs(upd - ref).max() <= common.MAX_ERR_FRAC * np.abs(ref).max() + ulp, f"fused step, layer {l}"
+        # free-running: same routing at every layer
+        assert np.array_equal(idx_all[l], ref_idx), f"free-running layer {l}"
+        fr_max, fr_l2 = common.ffn_errors(h_dev_layers[l], hs[l + 1])
+        report.append(f"{l} {gap:.4f} {int(golden[l]['n_int4'])} {tf_max:.3e} {tf_l2:.3e} {fr_max:.3e} {fr_l2:.3e} "
+                      f"{golden[l]['fr_exact_max']:.3e} {golden[l]['fr_exact_l2']:.3e}")
         if l % 8 == 7:
-            _say(f"chain: oracle through layer {l}, gap {gap:.3e}")
-    _say(f"chain: first layer with a top-3 gap below 1e-2: {first_unsafe}")
-    if first_unsafe is None:
-        # Free-running bar.  Each block, fed the oracle's own input, meets the per-block bar above.  Left to
-        # run, block l sees the deviations of blocks 0..l-1 on its input; the residual path carries them on
-        # with unit gain and the L per-block deviations are independent, so they add in quadrature: the bar
-        # on the final hidden state is sqrt(L) times the per-block one (routing must still agree everywhere).
-        max_frac, rel_l2 = common.ffn_errors(h_dev, hs[-1])
-        _say(f"chain: free-running max|err|/max|ref|={max_frac:.3e} relL2={rel_l2:.3e}")
-        grow = float(np.sqrt(L))
-        assert max_frac <= common.MAX_ERR_FRAC * grow and rel_l2 <= common.REL_L2 * grow
-    else:
-        assert first_unsafe >= 4, "seed gives too short a comparable prefix; pick another seed"
+            _say(f"chain: oracle through layer {l}, gap {gap:.3e}, free-running relL2 {fr_l2:.3e}")
+    _say("\n".join(report))
+    out_dir = Path(__file__).resolve().parents[1] / "gpurun_out"
+    if out_dir.is_dir():
+        (out_dir / "chain_32_layers_parity.txt").write_text("\n".join(report) + "\n")
+    # Free-running bar: twice the deviation of the oracle's fp32-accumulator mode (4-bit weights unrounded, as the
+    # one-token kernels evaluate them) from the double oracle at the last layer of the same trajectory.
+    max_frac, rel_l2 = common.ffn_errors(h_dev, hs[-1])
+    bar_max, bar_l2 = 2.0 * golden[-1]["fr_exact_max"], 2.0 * golden[-1]["fr_exact_l2"]
+    _say(f"chain: free-running max|err|/max|ref|={max_frac:.3e} (bar {bar_max:.3e}) relL2={rel_l2:.3e} (bar {bar_l2:.3e})")
+    assert max_frac <= bar_max and rel_l2 <= bar_l2

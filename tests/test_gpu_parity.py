@@ -218,6 +218,24 @@ def test_expert_ffn_shape_agnostic_kernels(orc, n):
         assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n={n} e={e}")
 
 
+def test_expert_ffn_single_row_runs_the_one_token_kernels(orc):
+    """n = 1 at a shape the batch-1 kernels take (d and f multiples of 2048): the expert alone, before gating and
+    weighted average, for a 16-bit and a 4-bit expert; the workspace status stays clear."""
+    cfg = common.DECODE_SMALL
+    wl = build_workload(cfg, orc, experts_needed=(0, 1))
+    assert not wl.experts[0].int4 and wl.experts[1].int4
+    layer = device_layer(wl)
+    ws = mm.alloc_workspace(layer, 1)
+    for seed in (43, 44):
+        x = synth.normal_f16((1, cfg.d), 1.0, seed, synth.x_stream(0))
+        for e in (0, 1):
+            _say(f"expert_ffn one-token kernels cfg={cfg.name} seed={seed} expert={e}")
+            y = torch.full((1, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+            mm.moe_expert_ffn_mixed(layer, e, dev(x), y, ws)
+            assert mm.moe_read_status(ws) == 0
+            assert_ffn_close(y.cpu().numpy(), orc.expert_ffn(wl.experts[e], x), f"{cfg.name} n=1 e={e}")
+
+
 def test_expert_ffn_identity_weights_exact_structure(orc):
     """One-entry matrices: catches a transposed operand or swapped w1/w3 in the kernels."""
     d, f = 128, 192
@@ -396,16 +414,21 @@ def _chain_workloads(cfg, orc, n_layers):
 
 
 def _oracle_trajectory(orc, wls, h0, g, eps, k):
-    """Oracle hidden states, indices and, per token, the smallest top-(k+1) adjacent logit gap over all layers."""
-    hs, idxs = [h0], []
+    """Oracle hidden states, normed block inputs, block outputs (double), indices and, per token, the smallest
+    top-(k+1) adjacent logit gap over all layers."""
+    hs, normeds, outs, idxs = [h0], [], [], []
     gap = np.full(h0.shape[0], np.inf)
     for wl in wls:
         h1, idx, gate, normed = orc.chain_layer(hs[-1], g, eps, wl.wg, wl.experts, k)
+        out, idx2, _ = orc.layer_forward(normed, wl.wg, wl.experts, k)
+        assert np.array_equal(idx, idx2)
         lg = np.sort(common.logits_f64(normed, wl.wg, None), axis=1)[:, ::-1]
         gap = np.minimum(gap, (lg[:, :k] - lg[:, 1:k + 1]).min(axis=1))
         hs.append(h1)
+        normeds.append(normed)
+        outs.append(out)
         idxs.append(idx)
-    return hs, idxs, gap
+    return hs, normeds, outs, idxs, gap
 
 
 @pytest.mark.parametrize("cfg,n_layers", [(TINY, 5), (common.Config("medium1", 1024, 2816, 8, 2, 1, ()), 3)],
@@ -419,7 +442,7 @@ def test_chain_teacher_forced_and_free_running(orc, cfg, n_layers):
         c = common.Config(cfg.name, cfg.d, cfg.f, cfg.E, cfg.k, cfg.T, (), seed=seed)
         wls = _chain_workloads(c, orc, n_layers)
         h0 = synth.normal_f16((c.T, c.d), 1.0, seed, synth.x_stream(0))
-        hs, idxs, gap = _oracle_trajectory(orc, wls, h0, g, eps, c.k)
+        hs, normeds, outs, idxs, gap = _oracle_trajectory(orc, wls, h0, g, eps, c.k)
         safe_tok = gap > 1e-2
         if safe_tok.sum() * 2 >= c.T:
             break
@@ -439,8 +462,14 @@ def test_chain_teacher_forced_and_free_running(orc, cfg, n_layers):
         ok = (lg[:, :c.k] - lg[:, 1:c.k + 1]).min(axis=1) > 1e-3
         assert ok.any()
         assert np.array_equal(idx_out.cpu().numpy()[0][ok], idxs[l][ok])
-        # compare the update (what the block computes); the stored h is rounded to fp16 on both sides, which
-        # can move an element by one unit in its last place
+        # the block alone on the oracle's normed input: both criteria of the block tolerance
+        blk = torch.empty((c.T, c.d), dtype=torch.float16, device="cuda")
+        idx_blk = torch.empty((c.T, c.k), dtype=torch.int32, device="cuda")
+        mm.moe_layer_forward(layers[l], dev(normeds[l]), blk, ws, idx_blk, None)
+        assert np.array_equal(idx_blk.cpu().numpy()[ok], idxs[l][ok])
+        assert_ffn_close(blk.cpu().numpy()[ok], outs[l][ok], f"teacher-forced block {l}")
+        # extra: the fused RMSNorm + block + residual step.  The stored h is rounded to fp16 on both sides, which
+        # can move an element by one unit in its last place on top of the block's own deviation
         upd = h.cpu().numpy().astype(np.float64)[ok] - hs[l].astype(np.float64)[ok]
         ref = hs[l + 1].astype(np.float64)[ok] - hs[l].astype(np.float64)[ok]
         ulp = 2.0 ** -10 * np.abs(hs[l + 1].astype(np.float64)).max()
@@ -534,7 +563,7 @@ def test_decode_path_non_resident_and_chain(orc):
     # three chained blocks at this shape: RMSNorm -> decode kernels with the residual fused into the down-projection
     eps, g = 1e-5, np.ones(cfg.d, dtype=np.float16)
     wls = _chain_workloads(cfg, orc, 3)
-    hs, idxs, gap = _oracle_trajectory(orc, wls, x, g, eps, cfg.k)
+    hs, _, _, idxs, gap = _oracle_trajectory(orc, wls, x, g, eps, cfg.k)
     assert gap[0] > 1e-2, "pick another token stream"
     layers = [device_layer(w) for w in wls]
     h = dev(x)

@@ -1,0 +1,69 @@
+"""The scalars the paper prints (tests/golden/paper_constants.txt) against what the shapes, the planner and this
+library's formats imply.  Host only."""
+from pathlib import Path
+
+import pytest
+
+from oracle import planner_oracle as po
+from paper_2407_14417_amd import binding as mm
+
+GOLDEN = Path(__file__).resolve().parent / "golden" / "paper_constants.txt"
+D_MODEL, D_FF = 4096, 14336                       # Mixtral 8x7B expert shape (§4.1)
+E16_BYTES = 3 * D_MODEL * D_FF * 2                # three fp16 matrices
+E4_BYTES = 3 * (D_MODEL * D_FF // 2 + 2 * (D_MODEL * D_FF // 64) * 2)     # codes + fp16 scale and zero per 64
+
+
+@pytest.fixture(scope="module")
+def paper():
+    vals = {}
+    for line in GOLDEN.read_text().splitlines():
+        line = line.split("#")[0].strip()
+        if line:
+            name, value = (p.strip() for p in line.split("="))
+            vals[name] = float(value)
+    return vals
+
+
+def test_expert_count_and_size(paper):
+    assert paper["n_layers"] * paper["experts_per_layer"] == paper["total_experts"] == 256
+    # §4.1's 336 MB per 16-bit expert is three 4096 x 14336 fp16 matrices, counted in MiB
+    assert E16_BYTES == paper["expert_size_MB"] * 2 ** 20
+    assert E4_BYTES == 99_090_432
+
+
+def test_table1_sizes_follow_from_the_parts(paper):
+    # all-16-bit model = non-expert part + 256 experts, within the table's rounding and unit convention
+    total = paper["non_expert_size_GB"] * 1e9 + paper["total_experts"] * E16_BYTES
+    assert abs(total / 1e9 - paper["model_size_16bit_GB"]) <= 0.015 * paper["model_size_16bit_GB"]
+    # the homogeneous rows scale with the bit width
+    assert abs(paper["model_size_16bit_GB"] / paper["model_size_8bit_GB"] - 2.0) < 1e-3
+    assert abs(paper["model_size_16bit_GB"] / paper["model_size_4bit_GB"] - 4.0) < 1e-3
+    # smallest mixed model = every expert 4-bit, non-expert part 16-bit: the implied width of the paper's 4-bit data
+    # type is a little above 4 bits per weight; this library's format (4.5 bits) lands within 10 % of that size
+    experts16 = paper["model_size_16bit_GB"] - paper["non_expert_size_GB"]
+    bits = (paper["model_size_mixed_min_GB"] - paper["non_expert_size_GB"]) / experts16 * 16
+    assert 4.0 < bits < 4.25
+    ours = paper["non_expert_size_GB"] * 1e9 + paper["total_experts"] * E4_BYTES
+    assert paper["model_size_mixed_min_GB"] < ours / 1e9 < 1.1 * paper["model_size_mixed_min_GB"]
+    assert E4_BYTES * 16 / E16_BYTES == 4.5
+
+
+def test_expert_copy_time_is_a_pcie_gen4_rate(paper):
+    rate = E16_BYTES / (paper["expert_transfer_ms"] * 1e-3) / 1e9
+    assert 8.0 < rate < 32.0                       # GB/s: below the 31.5 GB/s of a Gen4 x16 link, above half a Gen3 one
+
+
+def test_eq1_promotion_cost(paper):
+    """Eq. 1: every expert promoted from 4-bit to 16-bit costs `factor` 4-bit expert sizes on top of the all-4-bit
+    model; the planner oracle and the library's planner both step exactly there."""
+    factor = int(paper["eq1_promotion_cost_in_4bit_experts"])
+    ne, n = int(paper["non_expert_size_GB"] * 1e9), int(paper["total_experts"])
+    s16 = int(paper["expert_size_MB"]) * 10 ** 6
+    s4 = s16 // 4
+    assert s16 - s4 == factor * s4                 # where the factor comes from: a 16-bit expert is four 4-bit ones
+    base = ne + n * s4
+    for m in (1, 2, 17, 255, 256):
+        for mem, want in ((base + factor * s4 * m - 1, m - 1), (base + factor * s4 * m, m)):
+            assert po.num_e16_eq1(mem, ne, n, s4) == want
+            res, _, _ = mm.moe_plan(mem, ne, s16, s4, n, mm.PREFER_THROUGHPUT)
+            assert res.num_e16 == want
