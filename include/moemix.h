@@ -49,6 +49,7 @@ extern "C" {
 #define MOE_GROUP 64
 #define MOE_MAX_EXPERTS 32
 #define MOE_MAX_TOPK 8
+#define MOE_STATIC_SCRATCH_BYTES (8u << 20) /* scratch held by the library for moe_layer_forward_static */
 
 typedef enum {
     MOE_OK = 0,
@@ -142,6 +143,21 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
                       float* topk_gate_out, void* ws, size_t ws_bytes, moe_stream_t stream);
 
 /*
+ * moe_layer_forward for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels and same
+ * results as moe_layer_forward, minus `ws`: the scratch is a fixed array of MOE_STATIC_SCRATCH_BYTES inside
+ * the library, one per GPU, held until the process ends.  The call allocates nothing and frees nothing.
+ * Fails with MOE_EWORKSPACE when moe_workspace_bytes(layer, T) exceeds MOE_STATIC_SCRATCH_BYTES (at the
+ * Mixtral shape, d_model 4096, d_ff 14336, top-2: up to 32 tokens fit).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (two streams, two
+ * threads) race; serialize them or use moe_layer_forward with separate workspaces.  The status bits of the
+ * most recent call are read with moe_read_status(NULL, stream, &bits) while that GPU is current.
+ */
+size_t moe_static_scratch_bytes(void);
+int moe_layer_forward_static(const moe_layer* layer, const void* x, int T, void* out, int32_t* topk_idx_out,
+                             float* topk_gate_out, moe_stream_t stream);
+
+/*
  * Expert-miss path (§3: device memory is set aside as a swap space that receives an expert from the host when
  * a token is routed to an expert that is not on the device; §4.1: the copy of an expert is what offloading costs).  Experts of `layer` with resident == 0 live in PINNED
  * host memory; when the gating network routes a token to one of them it is copied into a slot of a device-side
@@ -213,7 +229,8 @@ int moe_quantize_int4(const void* w_fp16, int out, int in, void* packed, void* s
 int moe_synth_fill_f16(void* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale,
                        int kind, moe_stream_t stream);
 
-/* Waits for `stream`, then reads the status word of `ws`: OR of (1 << -code) over the device-side conditions
+/* Waits for `stream`, then reads the status word of `ws` (NULL: of the library's own scratch on the current GPU,
+ * as used by moe_layer_forward_static): OR of (1 << -code) over the device-side conditions
  * raised by the most recent moe_layer_forward / moe_chain_forward / moe_permute call that used `ws`
  * (bit 3: a routed expert was not resident; bit 1: an expert index outside [0, n_experts)). */
 int moe_read_status(void* ws, moe_stream_t stream, int* status_bits);

@@ -24,7 +24,7 @@ EXPORTS = (
     "moe_workspace_bytes", "moe_route", "moe_permute", "moe_expert_ffn_mixed", "moe_layer_forward",
     "moe_chain_forward", "moe_dequant_int4", "moe_quantize_int4", "moe_synth_fill_f16", "moe_read_status",
     "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan", "moe_swap_slot_bytes", "moe_layer_forward_swap",
-    "moe_stream_read",
+    "moe_stream_read", "moe_static_scratch_bytes", "moe_layer_forward_static",
 )
 
 
@@ -100,10 +100,14 @@ def lib():
         L.moe_layer_forward_swap.argtypes = [LP, ctypes.POINTER(CSwap), vp, i32, vp, vp, vp, vp, sz, vp,
                                              ctypes.POINTER(ctypes.c_int32)]
         L.moe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.moe_static_scratch_bytes.argtypes = []
+        L.moe_static_scratch_bytes.restype = sz
+        L.moe_layer_forward_static.argtypes = [LP, vp, i32, vp, vp, vp, vp]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_version.restype = i32
         for name in EXPORTS:
-            if name not in ("moe_workspace_bytes", "moe_last_error", "moe_version", "moe_swap_slot_bytes"):
+            if name not in ("moe_workspace_bytes", "moe_last_error", "moe_version", "moe_swap_slot_bytes",
+                            "moe_static_scratch_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -203,6 +207,15 @@ def moe_layer_forward(layer: Layer, x, out, ws, topk_idx_out=None, topk_gate_out
                                    _ptr(topk_gate_out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
 
 
+def moe_static_scratch_bytes() -> int:
+    return int(lib().moe_static_scratch_bytes())
+
+
+def moe_layer_forward_static(layer: Layer, x, out, topk_idx_out=None, topk_gate_out=None) -> None:
+    _check(lib().moe_layer_forward_static(ctypes.byref(layer.c), _ptr(x), x.shape[0], _ptr(out), _ptr(topk_idx_out),
+                                          _ptr(topk_gate_out), _stream()))
+
+
 class Swap:
     """Swap space and host-side expert copies for moe_layer_forward_swap.  `host_experts[e]` is an Expert whose
     tensors are pinned host tensors (or None for experts that are resident in `layer`)."""
@@ -262,6 +275,7 @@ def moe_synth_fill_f16(dst, first: int, seed: int, stream_id: int, scale: float,
 
 
 def moe_read_status(ws) -> int:
+    """Status bits of the last call on workspace ``ws`` (None: of the last moe_layer_forward_static call)."""
     v = ctypes.c_int(0)
     _check(lib().moe_read_status(_ptr(ws), _stream(), ctypes.byref(v)))
     return v.value

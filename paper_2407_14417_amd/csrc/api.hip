@@ -1,6 +1,7 @@
 // C-ABI entry points of libmoemix (declared and documented in include/moemix.h): argument
 // checks, workspace carving, kernel sequencing.  No allocation, no synchronization except in
 // moe_read_status.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -241,6 +242,61 @@ int moe_layer_forward(const moe_layer* layer, const void* x, int T, void* out, i
                       (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------------- the block without a caller workspace
+
+namespace {
+
+// Scratch of moe_layer_forward_static: one array per GPU, held until the process ends.
+constexpr size_t kStaticScratchBytes = MOE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle).  Looked up once per
+// device, with that device current; 0 = not looked up yet.
+constexpr int kMaxDevices = 64;
+std::atomic<uintptr_t> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(MOE_EHIP, "HIP: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_EHIP, "device %d outside [0, %d)", dev, kMaxDevices);
+    uintptr_t p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !sym)
+            return fail(MOE_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        p = (uintptr_t)sym;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread finds the same address
+    }
+    *out = (void*)p;
+    return MOE_OK;
+}
+
+}  // namespace
+
+size_t moe_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int moe_layer_forward_static(const moe_layer* layer, const void* x, int T, void* out, int32_t* topk_idx_out,
+                             float* topk_gate_out, moe_stream_t stream) {
+    if (int rc = check_layer(layer)) return rc;
+    if (!x || !out) return fail(MOE_EINVAL, "moe_layer_forward_static: NULL argument");
+    if (T < 1) return fail(MOE_ESHAPE, "moe_layer_forward_static: T=%d < 1", T);
+    const size_t need = moe_workspace_bytes(layer, T);
+    if (need == 0 || need > kStaticScratchBytes)
+        return fail(MOE_EWORKSPACE, "moe_layer_forward_static: %d tokens of this layer need %zu bytes of scratch, the "
+                    "library holds %zu; use moe_layer_forward with a workspace", T, need, kStaticScratchBytes);
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    Workspace w;
+    if (int rc = check_ws(layer, T, ws, kStaticScratchBytes, &w)) return rc;
+    const DevExperts table = device_table(layer);
+    // the scratch keeps the last call's contents: the status word is cleared by the gating kernel, every other
+    // region is written before it is read
+    return layer_body(layer, table, (const half_t*)x, T, nullptr, 0.0f, nullptr, (half_t*)out, topk_idx_out, topk_gate_out, w,
+                      true, (hipStream_t)stream);
+}
+
 // ---------------------------------------------------------------- expert-miss path
 
 namespace {
@@ -455,7 +511,10 @@ int moe_stream_read(const void* src, size_t bytes, void* sink, moe_stream_t stre
 }
 
 int moe_read_status(void* ws, moe_stream_t stream, int* status_bits) {
-    if (!ws || !status_bits) return fail(MOE_EINVAL, "moe_read_status: NULL argument");
+    if (!status_bits) return fail(MOE_EINVAL, "moe_read_status: NULL argument");
+    if (!ws) {      // the library's own scratch on the current device (moe_layer_forward_static)
+        if (int rc = static_scratch(&ws)) return rc;
+    }
     int32_t v = 0;
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e == hipSuccess) e = hipMemcpy(&v, ws, sizeof(v), hipMemcpyDeviceToHost);
