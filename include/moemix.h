@@ -239,6 +239,9 @@ int moe_read_status(void* ws, moe_stream_t stream, int* status_bits);
  * Measurement hook: the next launch of kernel `kernel` made by this thread is bracketed by
  * hipEventRecord(start_event) / hipEventRecord(stop_event) on the stream it is launched on (one shot;
  * arm again for the next launch).  Events are hipEvent_t created by the caller with timing enabled.
+ * Both events NULL: a bracket that has been armed and not used yet is dropped.  A call on one token launches no
+ * separate gating kernel (the gating network runs inside the up-projection launch): MOE_KERNEL_ROUTE then never
+ * fires.  An armed bracket must not meet a launch that is being captured into a graph.
  */
 enum { MOE_KERNEL_ROUTE = 0,   /* gating (with the RMSNorm of the chained configuration) */
        MOE_KERNEL_PERMUTE = 1, /* grouping */

@@ -284,7 +284,8 @@ def moe_read_status(ws) -> int:
 KERNEL_ROUTE, KERNEL_PERMUTE, KERNEL_UP, KERNEL_DOWN, KERNEL_COMBINE, KERNEL_STREAM_READ = range(6)
 
 
-def moe_trace_kernel(kernel: int, start_event: int, stop_event: int) -> None:
+def moe_trace_kernel(kernel: int, start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """Arms a one-shot event bracket around the next launch of ``kernel``; (None, None) drops an unused one."""
     _check(lib().moe_trace_kernel(kernel, start_event, stop_event))
 
 

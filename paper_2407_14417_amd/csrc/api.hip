@@ -100,15 +100,19 @@ int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int
                const half_t* residual, half_t* out, int32_t* idx_out, float* gate_out, const Workspace& w,
                bool reset_status, hipStream_t st) {
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
-    launch_route(x, (const half_t*)L->w_gate, L->gate_bias, T, d, E, k, w.idx, w.gate, idx_out, gate_out,
-                 reset_status ? w.status : nullptr, st, rms_gain, eps, w.xn);
-    if (rms_gain) x = w.xn;
     if (T == 1 && decode_shape_ok(d, f)) {
-        // batch-1 decode: no grouping needed, the weighted average is fused into the down-projection
-        launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, kDecodeUpBlocks, st);
+        // batch-1 decode: two launches.  The gating network (and the RMSNorm of the chain) runs inside the
+        // up-projection launch, no grouping is needed, the weighted average is fused into the down-projection.
+        // The up-projection launch clears the word it is given: the status word for the first block of a call, a
+        // spare word of the status region for later blocks of a chain, which must keep what earlier blocks raised.
+        const GateArgs ga{(const half_t*)L->w_gate, L->gate_bias, E, rms_gain, eps, w.idx, w.gate, idx_out, gate_out};
+        launch_decode_up(table, nullptr, x, d, f, k, w.h, reset_status ? w.status : w.status + 1, kDecodeUpBlocks, st, &ga);
         launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, residual, out, w.status, st);
         return check_hip(st);
     }
+    launch_route(x, (const half_t*)L->w_gate, L->gate_bias, T, d, E, k, w.idx, w.gate, idx_out, gate_out,
+                 reset_status ? w.status : nullptr, st, rms_gain, eps, w.xn);
+    if (rms_gain) x = w.xn;
     launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
     RowMap rows{w.offsets, w.perm, k, -1, 0};
     const size_t split_stride = (size_t)T * k * d;
@@ -138,6 +142,7 @@ thread_local Trace g_trace[kKernelCount];   // one slot per kernel id: several k
 }  // namespace
 
 void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop) { g_trace[kernel] = Trace{true, start, stop}; }
+void trace_disarm(int kernel) { g_trace[kernel] = Trace{}; }
 
 TraceScope::TraceScope(int kernel_, hipStream_t st_) : kernel(kernel_), st(st_) {
     if (g_trace[kernel].armed) (void)hipEventRecord(g_trace[kernel].start, st);
@@ -155,8 +160,12 @@ TraceScope::~TraceScope() {
 extern "C" {
 
 int moe_trace_kernel(int kernel, void* start_event, void* stop_event) {
-    if (kernel < 0 || kernel >= kKernelCount || !start_event || !stop_event)
-        return fail(MOE_EINVAL, "moe_trace_kernel: bad kernel id or NULL event");
+    if (kernel < 0 || kernel >= kKernelCount) return fail(MOE_EINVAL, "moe_trace_kernel: bad kernel id %d", kernel);
+    if (!start_event && !stop_event) {
+        trace_disarm(kernel);
+        return MOE_OK;
+    }
+    if (!start_event || !stop_event) return fail(MOE_EINVAL, "moe_trace_kernel: one event is NULL");
     trace_arm(kernel, (hipEvent_t)start_event, (hipEvent_t)stop_event);
     return MOE_OK;
 }

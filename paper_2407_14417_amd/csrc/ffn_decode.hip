@@ -8,6 +8,7 @@
 //   sum_c (q_c*s + z) x_c = s * sum_c q_c x_c + z * sum_c x_c,
 // with the per-lane sums of x precomputed once, so a weight costs about 1.3 vector instructions.
 #include "common.hpp"
+#include "gating.hpp"
 #include "kernels.hpp"
 
 namespace moemix {
@@ -24,6 +25,30 @@ struct ActI4 {
     float c1;          // 1024 * (sum of even-column x + sum of odd-column x / 16): offset of the biased codes
     float c2;          // sum of the 32 x: multiplies the group zero
 };
+
+// The 32 activations of a lane as loaded (four 128-bit pieces), before they are paired up.
+struct RawI4 {
+    half8_t v[4];
+};
+
+__device__ __forceinline__ void request_act_i4(const half_t* __restrict__ src, RawI4& raw) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) raw.v[j] = *(const half8_t*)(src + 8 * j);
+}
+
+__device__ __forceinline__ void pair_act_i4(const RawI4& raw, ActI4& a) {
+    float se = 0.0f, so = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const half8_t v = raw.v[j];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a.p[j][q] = half2_t{v[q], v[q + 4]};
+        se += ((float)v[0] + (float)v[2]) + ((float)v[4] + (float)v[6]);
+        so += ((float)v[1] + (float)v[3]) + ((float)v[5] + (float)v[7]);
+    }
+    a.c1 = 1024.0f * se + 64.0f * so;
+    a.c2 = se + so;
+}
 
 __device__ __forceinline__ void load_act_i4(const half_t* __restrict__ src, ActI4& a) {
     float se = 0.0f, so = 0.0f;
@@ -128,17 +153,68 @@ constexpr int kUpRowsI4 = 2;                    // rows per register buffer of t
 constexpr int kUpBufsI4 = 2;                    // register buffers in the ring of the 4-bit path
 constexpr uint32_t kMinUnitsPerWave = 100;      // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short
 
-template <int NCH>   // d_model / 2048
+// ROUTE: the gating network (with the RMSNorm of the chained configuration) runs inside this launch.  A separate
+// gating launch is a chain of latencies (token -> logits -> reduction -> top-k -> launch boundary) during which
+// device memory sits idle; here every workgroup evaluates the gating network for the one token by itself, from
+// the 64 KB gate matrix that all of them read out of L2, and goes straight on to its share of the weights.
+// Workgroup 0 also writes the routing result for the down-projection launch and for the caller.
+template <int NCH, bool ROUTE>   // NCH = d_model / 2048
 __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
                                                          const half_t* __restrict__ x, int f, int k,
-                                                         half_t* __restrict__ h, int32_t* status) {
+                                                         half_t* __restrict__ h, int32_t* status, const GateArgs ga) {
     constexpr int d = NCH * 2048;
     const int lane = threadIdx.x & 63;
+    __shared__ __align__(16) half_t xs[ROUTE ? d : 8];      // block input (after the RMSNorm, if any)
+    __shared__ float logit_s[MOE_MAX_EXPERTS];
+    // the routed experts, 5 bits per slot (k <= 8 slots, E <= 32 experts), uniform
+    uint64_t routed = 0;
+    if (ROUTE) {
+        // nothing of this launch raises status bits (the down-projection launch reports experts that cannot run),
+        // so the word can be cleared here without a race
+        if (blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
+        uint4_t xv[4 * NCH];
+        gate_load_row<4 * NCH>(x, d, lane, xv);
+        if (ga.rms_gain) gate_rmsnorm<4 * NCH>(xv, ga.rms_gain, d, ga.eps, lane);
+        if (wave_index() == 0) {
+#pragma unroll
+            for (int j = 0; j < 4 * NCH; ++j) *(uint4_t*)(xs + (lane + 64 * j) * 8) = xv[j];
+        }
+        for (int e = wave_index(); e < ga.E; e += 4) {
+            const float l = gate_logit<4 * NCH>(xv, ga.wg + (size_t)e * d, d, lane);
+            if (lane == 0) logit_s[e] = l + (ga.bias ? ga.bias[e] : 0.0f);
+        }
+        __syncthreads();
+        int sel[MOE_MAX_TOPK];
+        float lsel[MOE_MAX_TOPK];
+        gate_select(logit_s, ga.E, k, sel, lsel);
+#pragma unroll
+        for (int s = 0; s < MOE_MAX_TOPK; ++s)
+            if (s < k) routed |= (uint64_t)(uint32_t)sel[s] << (5 * s);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            float g[MOE_MAX_TOPK];
+            gate_weights(lsel, k, g);
+#pragma unroll
+            for (int s = 0; s < MOE_MAX_TOPK; ++s) {
+                if (s < k) {
+                    ga.idx_ws[s] = sel[s];
+                    ga.gate_ws[s] = g[s];
+                    if (ga.idx_out) ga.idx_out[s] = sel[s];
+                    if (ga.gate_out) ga.gate_out[s] = g[s];
+                }
+            }
+        }
+    } else {
+        for (int s = 0; s < k; ++s) routed |= (uint64_t)(uint32_t)idx[s] << (5 * s);
+    }
+    routed = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(routed >> 32)) << 32) |
+             (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)routed);
+    auto expert_of = [&](int s) { return (int)((routed >> (5 * s)) & 31u); };
+    const half_t* xin = ROUTE ? xs : x;
     // 32-bit arithmetic throughout: total <= 8 slots * 16384 rows * 32 units
     // the wavefront index goes through a scalar register: everything derived from it (row ranges, row base
     // addresses) is then uniform, and the loads below take the scalar-base + 32-bit lane-offset form
     uint32_t total = 0;
-    for (int s = 0; s < k; ++s) total += (uint32_t)f * (ex.e[idx[s]].prec == MOE_PREC_INT4G64 ? 9u : 32u);
+    for (int s = 0; s < k; ++s) total += (uint32_t)f * (ex.e[expert_of(s)].prec == MOE_PREC_INT4G64 ? 9u : 32u);
     // A wavefront needs a dozen rows or so for its load pipeline to reach a steady state.  When the routed
     // experts are small (all 4-bit), half the workgroups take all the work and the others leave at once: the
     // launch shape is fixed on the host before the routing result exists, the work is only known here.
@@ -151,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     const uint32_t hi = lo + share + (gw < extra ? 1u : 0u);
     uint32_t base = 0;
     for (int s = 0; s < k; ++s) {
-        const DevExpert& ee = ex.e[idx[s]];
+        const DevExpert& ee = ex.e[expert_of(s)];
         const bool int4 = ee.prec == MOE_PREC_INT4G64;
         const uint32_t span = (uint32_t)f * (int4 ? 9u : 32u);
         // rows whose first cost unit falls in [lo, hi): ceil((lo - base) / cost) .. ceil((hi - base) / cost)
@@ -161,11 +237,8 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
         const int r0 = __builtin_amdgcn_readfirstlane((int)(int4 ? (l + 8u) / 9u : (l + 31u) / 32u));
         const int r1 = __builtin_amdgcn_readfirstlane((int)(int4 ? (u + 8u) / 9u : (u + 31u) / 32u));
         base += span;
-        if (r0 >= r1 || ee.resident == kDeferred) continue;
-        if (!ee.resident || !ee.w1.data) {
-            if (lane == 0) atomicOr(status, kStatusNotResident);
-            continue;
-        }
+        // an expert that cannot run is left out here and reported by the down-projection launch
+        if (r0 >= r1 || ee.resident != 1 || !ee.w1.data) continue;
         half_t* hs = h + (size_t)s * f;
         if (int4) {
             ActI4 act[NCH];
@@ -252,7 +325,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
             __builtin_amdgcn_sched_barrier(0);
             // the first weight rows are requested before the token: they come from HBM, the token from L2
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) load_act_i4(x + c * 2048 + lane * 32, act[c]);
+            for (int c = 0; c < NCH; ++c) load_act_i4(xin + c * 2048 + lane * 32, act[c]);
             publish_group();
             load_group(r0 + G);
             __builtin_amdgcn_sched_barrier(0);
@@ -300,7 +373,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
             load_row(A, w1, r0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int c = 0; c < NL; ++c) load_act_f16(x + c * 512 + lane * 8, act[c]);
+            for (int c = 0; c < NL; ++c) load_act_f16(xin + c * 512 + lane * 8, act[c]);
             for (int r = r0; r < r1; ++r) {
                 load_row(B, w3, r);
                 __builtin_amdgcn_sched_barrier(0);
@@ -456,15 +529,22 @@ __global__ void single_route_kernel(int32_t* idx, float* gate, int expert) {
 
 bool decode_shape_ok(int d, int f) { return d % 2048 == 0 && d <= 8192 && f % 2048 == 0 && f <= 16384 && d % kDownRows == 0; }
 
-void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
-                      int32_t* status, int blocks, hipStream_t st) {
-    TraceScope trace(kKernelUp, st);
+template <bool ROUTE>
+static void launch_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
+                      int32_t* status, int blocks, const GateArgs& ga, hipStream_t st) {
     switch (d / 2048) {
-        case 1: decode_up_kernel<1><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status); break;
-        case 2: decode_up_kernel<2><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status); break;
-        case 3: decode_up_kernel<3><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status); break;
-        default: decode_up_kernel<4><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status); break;
+        case 1: decode_up_kernel<1, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        case 2: decode_up_kernel<2, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        case 3: decode_up_kernel<3, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        default: decode_up_kernel<4, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
     }
+}
+
+void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
+                      int32_t* status, int blocks, hipStream_t st, const GateArgs* gating) {
+    TraceScope trace(kKernelUp, st);
+    if (gating) launch_up<true>(ex, idx, x, d, f, k, h, status, blocks, *gating, st);
+    else launch_up<false>(ex, idx, x, d, f, k, h, status, blocks, GateArgs{}, st);
 }
 
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,

@@ -47,8 +47,23 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
 
 // Batch-1 decode path (one token): shapes it covers, and its two kernels.
 bool decode_shape_ok(int d, int f);
+// Gating network evaluated inside the up-projection launch (one token): gate matrix [E, d], optional bias,
+// optional RMSNorm of the token first (rms_gain != null); the routing result goes to idx_ws / gate_ws [top_k] for
+// the down-projection launch and, if wanted, to idx_out / gate_out.  The launch then also clears the status word.
+struct GateArgs {
+    const half_t* wg;
+    const float* bias;
+    int E;
+    const half_t* rms_gain;
+    float eps;
+    int32_t* idx_ws;
+    float* gate_ws;
+    int32_t* idx_out;
+    float* gate_out;
+};
+// gating == null: the routing result is read from idx [top_k].
 void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
-                      int32_t* status, int blocks, hipStream_t st);
+                      int32_t* status, int blocks, hipStream_t st, const GateArgs* gating = nullptr);
 // out32 != null: the result is written there unrounded (fp32) instead of to `out`.
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
                         int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st,
@@ -82,6 +97,7 @@ enum KernelId { kKernelRoute = 0, kKernelPermute = 1, kKernelUp = 2, kKernelDown
 
 // One-shot event bracket around the next launch of a given kernel on this thread.
 void trace_arm(int kernel, hipEvent_t start, hipEvent_t stop);
+void trace_disarm(int kernel);
 struct TraceScope {
     int kernel;
     hipStream_t st;

@@ -1,112 +1,58 @@
 // Gating network with top-k selection (paper §1, §2.1) and the grouping of (token, slot)
 // pairs by expert.
 #include "common.hpp"
+#include "gating.hpp"
 #include "kernels.hpp"
 
 namespace moemix {
 
-// One workgroup per token.  Each thread takes 8-column chunks of the token row and of every
-// gate row (one 128-bit load each), accumulates E partial logits in fp32, the partials are
-// summed with wavefront shuffles and a 4-entry LDS step in a fixed order, then lane 0 runs
-// top_k selection passes (strict ">" keeps the lower index among equal logits) and the softmax
-// over the selected logits.
-template <int EMAX>
-__global__ __launch_bounds__(512) void route_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wg,
+// One workgroup of four wavefronts per token.  Every wavefront holds the whole token row (lane L the 8-column
+// chunks L, L + 64, ...), normalises it when the block input is RMSNorm(x) * gain, and evaluates the experts
+// w, w + 4, ... of the gate matrix, each as one wavefront-wide dot product (gating.hpp); thread 0 then runs the
+// top_k selection passes and the softmax over the selected logits.
+template <int NCHUNK>
+__global__ __launch_bounds__(256) void route_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wg,
                                                      const float* __restrict__ bias, int d, int E, int k,
                                                      int32_t* __restrict__ idx, float* __restrict__ gate,
                                                      int32_t* __restrict__ idx2, float* __restrict__ gate2,
                                                      int32_t* __restrict__ status, const half_t* __restrict__ rms_gain,
                                                      float eps, half_t* __restrict__ xn) {
-    __shared__ float part[8][EMAX];
-    __shared__ float logit[EMAX];
-    __shared__ float sq[8];
+    __shared__ float logit[MOE_MAX_EXPERTS];
     const int t = blockIdx.x;
-    const int tid = threadIdx.x, n_waves = blockDim.x >> 6;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     if (t == 0 && tid == 0 && status) *status = 0;   // status word describes the call that starts here
-    float acc[EMAX];
-#pragma unroll
-    for (int e = 0; e < EMAX; ++e) acc[e] = 0.0f;
-    const half_t* xr = x + (size_t)t * d;
-    // chained configuration: the block input is RMSNorm(x) * gain, rounded to fp16; it is written to xn for the
-    // expert kernels and used for the logits in the same pass
-    float inv = 1.0f;
+    uint4_t xv[NCHUNK];
+    gate_load_row<NCHUNK>(x + (size_t)t * d, d, lane, xv);
     if (rms_gain) {
-        float ss = 0.0f;
-        for (int c = tid * 8; c < d; c += blockDim.x * 8) {
-            const half8_t v = *(const half8_t*)(xr + c);
+        // chained configuration: the block input is RMSNorm(x) * gain, rounded to fp16; it is written to xn for the
+        // expert kernels and used for the logits in the same pass
+        gate_rmsnorm<NCHUNK>(xv, rms_gain, d, eps, lane);
+        if (wave == 0) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) ss += (float)v[j] * (float)v[j];
-        }
-        ss = wave_total(ss);
-        if (lane == 0) sq[wave] = ss;
-        __syncthreads();
-        float total = 0.0f;
-        for (int w = 0; w < n_waves; ++w) total += sq[w];
-        inv = 1.0f / sqrtf(total / (float)d + eps);
-    }
-    for (int c = tid * 8; c < d; c += blockDim.x * 8) {
-        uint4_t xv = *(const uint4_t*)(xr + c);
-        if (rms_gain) {
-            const half8_t v = __builtin_bit_cast(half8_t, xv), g = *(const half8_t*)(rms_gain + c);
-            half8_t o;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] = (half_t)((float)v[j] * inv * (float)g[j]);
-            *(half8_t*)(xn + (size_t)t * d + c) = o;
-            xv = __builtin_bit_cast(uint4_t, o);
-        }
-        uint4_t wv[EMAX];
-#pragma unroll
-        for (int e = 0; e < EMAX; ++e)
-            if (e < E) wv[e] = *(const uint4_t*)(wg + (size_t)e * d + c);
-#pragma unroll
-        for (int e = 0; e < EMAX; ++e) {
-            if (e < E) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[e] = __builtin_amdgcn_fdot2(as_half2(xv[j]), as_half2(wv[e][j]), acc[e], false);
+            for (int j = 0; j < NCHUNK; ++j) {
+                const int c = (lane + 64 * j) * 8;
+                if (c < d) *(uint4_t*)(xn + (size_t)t * d + c) = xv[j];
             }
         }
     }
-#pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-        if (e < E) {
-            const float s = wave_total(acc[e]);
-            if (lane == 0) part[wave][e] = s;
-        }
-    }
-    __syncthreads();
-    if (tid < E) {
-        float s = 0.0f;
-        for (int w = 0; w < n_waves; ++w) s += part[w][tid];
-        logit[tid] = s + (bias ? bias[tid] : 0.0f);
+    for (int e = wave; e < E; e += 4) {
+        const float l = gate_logit<NCHUNK>(xv, wg + (size_t)e * d, d, lane);
+        if (lane == 0) logit[e] = l + (bias ? bias[e] : 0.0f);
     }
     __syncthreads();
     if (tid == 0) {
-        uint32_t taken = 0;
         int sel[MOE_MAX_TOPK];
-        float lsel[MOE_MAX_TOPK];
-        for (int s = 0; s < k; ++s) {
-            int best = -1;
-            float lb = 0.0f;
-            for (int e = 0; e < E; ++e) {
-                if (taken & (1u << e)) continue;
-                const float l = logit[e];
-                if (best < 0 || l > lb) { best = e; lb = l; }
+        float lsel[MOE_MAX_TOPK], g[MOE_MAX_TOPK];
+        gate_select(logit, E, k, sel, lsel);
+        gate_weights(lsel, k, g);
+#pragma unroll
+        for (int s = 0; s < MOE_MAX_TOPK; ++s) {
+            if (s < k) {
+                idx[(size_t)t * k + s] = sel[s];
+                gate[(size_t)t * k + s] = g[s];
+                if (idx2) idx2[(size_t)t * k + s] = sel[s];
+                if (gate2) gate2[(size_t)t * k + s] = g[s];
             }
-            taken |= 1u << best;
-            sel[s] = best;
-            lsel[s] = lb;
-        }
-        float u[MOE_MAX_TOPK];
-        float denom = 0.0f;
-        for (int s = 0; s < k; ++s) { u[s] = expf(lsel[s] - lsel[0]); denom += u[s]; }
-        for (int s = 0; s < k; ++s) {
-            const float g = u[s] / denom;
-            idx[(size_t)t * k + s] = sel[s];
-            gate[(size_t)t * k + s] = g;
-            if (idx2) idx2[(size_t)t * k + s] = sel[s];
-            if (gate2) gate2[(size_t)t * k + s] = g;
         }
     }
 }
@@ -115,13 +61,13 @@ void launch_route(const half_t* x, const half_t* wg, const float* bias, int T, i
                   float* gate, int32_t* idx2, float* gate2, int32_t* status, hipStream_t st, const half_t* rms_gain,
                   float eps, half_t* xn) {
     TraceScope trace(kKernelRoute, st);
-    int threads = (d / 8 + 63) / 64 * 64;      // one 8-column chunk per thread when the row fits
-    threads = threads < 64 ? 64 : (threads > 512 ? 512 : threads);
-    if (E <= 8)
-        route_kernel<8><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps, xn);
+    if (d <= 2048)
+        route_kernel<4><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps, xn);
+    else if (d <= 4096)
+        route_kernel<8><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps, xn);
     else
-        route_kernel<MOE_MAX_EXPERTS><<<T, threads, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps,
-                                                               xn);
+        route_kernel<kGateMaxChunks><<<T, 256, 0, st>>>(x, wg, bias, d, E, k, idx, gate, idx2, gate2, status, rms_gain, eps,
+                                                          xn);
 }
 
 // One workgroup.  Wave w owns experts w, w+16: it walks all pairs in order, 64 at a time, and a

@@ -518,10 +518,12 @@ def test_decode_path_small_shape_all_precision_mixes(orc, k):
 @pytest.mark.parametrize("d,f,E,k,mask", [(2048, 2048, 3, 1, (0,)), (2048, 6144, 5, 3, (1, 2, 4)), (4096, 2048, 2, 2, (1,)),
                                           (2048, 4096, 4, 4, ()), (2048, 2048, 6, 2, (0, 1, 2, 3, 4, 5)),
                                           (6144, 2048, 2, 2, (0,)), (8192, 2048, 2, 1, (1,)), (8192, 4096, 2, 2, (0, 1)),
-                                          (2048, 16384, 2, 2, (1,))])
+                                          (2048, 16384, 2, 2, (1,)), (2048, 4096, 8, 8, (0, 2, 3, 5)),
+                                          (2048, 2048, 8, 5, (1, 2, 3, 6)), (2048, 2048, 32, 7, tuple(range(0, 32, 3)))])
 def test_decode_path_other_shapes(orc, d, f, E, k, mask):
     """Other shapes the batch-1 kernels take (d_model and d_ff multiples of 2048, d_model up to the limit of 8192):
-    two to six experts, top-1..4, all-16-bit, all-4-bit and mixed tables, three tokens each."""
+    two to 32 experts, top-1..8 (slots are taken two at a time: odd counts leave the last pair half empty),
+    all-16-bit, all-4-bit and mixed tables, three tokens each."""
     cfg = common.Config(f"dec_d{d}_f{f}_E{E}_k{k}", d, f, E, k, 1, mask, seed=7)
     wl = build_workload(cfg, orc)
     layer = device_layer(wl)
