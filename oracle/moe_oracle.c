@@ -26,7 +26,7 @@
  * Pins (tests marked "not gpu"): half conversions against numpy over all 65536
  * patterns and exact rational rounding; quantizer round-trip bound, exact group
  * minimum, constant groups, nibble order on a hand-written vector; dequantizer
- * against exact rational arithmetic; top-k against a full sort over all
+ * against exact rational arithmetic (the same pins for the 8-bit format); top-k against a full sort over all
  * permutations; gates against a library softmax (k = E), k = 1, shift
  * invariance, sum to one; expert against numpy float64 matmul and pure-Python
  * loops; one-hot and identical-expert layer identities; RMSNorm closed form.
@@ -184,6 +184,75 @@ int orc_dequant_int4(const uint8_t* q_packed, const uint16_t* scale, const uint1
     return 0;
 }
 
+/* ---------------------------------------------------------------- 8-bit format
+ *
+ * The paper's homogeneous comparison model holds every expert in 8 bits (§4, Table 1).  The 8-bit form of this
+ * build follows the 4-bit one: asymmetric uint8, groups of 64 consecutive columns of one row share an fp16 scale
+ * and an fp16 zero (the group minimum), one code per byte:
+ *   scale = fp16_rne( (fp32(max) - fp32(min)) / 255 ),  q = clamp( rint( (fp32(w) - fp32(zero)) / fp32(scale) ), 0, 255 )
+ *   w_hat = fp16_rne( fp32(q) * fp32(scale) + fp32(zero) )       (the product is exact in fp32: 8 bits times 11 bits)
+ */
+int orc_quantize_int8(const uint16_t* w, int out, int in, uint8_t* q_bytes, uint16_t* scale, uint16_t* zero) {
+    if (in % ORC_GROUP != 0 || out < 0) return -1;
+    const int groups = in / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < out; ++r) {
+        const uint16_t* wr = w + (size_t)r * in;
+        uint8_t* qr = q_bytes + (size_t)r * in;
+        for (int g = 0; g < groups; ++g) {
+            float mn = orc_half_to_float(wr[g * ORC_GROUP]);
+            float mx = mn;
+            uint16_t mn_bits = wr[g * ORC_GROUP];
+            for (int j = 1; j < ORC_GROUP; ++j) {
+                float v = orc_half_to_float(wr[g * ORC_GROUP + j]);
+                if (v < mn) { mn = v; mn_bits = wr[g * ORC_GROUP + j]; }
+                if (v > mx) mx = v;
+            }
+            volatile float range = mx - mn;        /* volatile: keep each step a rounded fp32 */
+            volatile float step = range / 255.0f;
+            uint16_t s_bits = orc_float_to_half(step);
+            float s = orc_half_to_float(s_bits);
+            scale[(size_t)r * groups + g] = s_bits;
+            zero[(size_t)r * groups + g] = mn_bits;
+            for (int j = 0; j < ORC_GROUP; ++j) {
+                int c = g * ORC_GROUP + j;
+                unsigned q = 0;
+                if (s != 0.0f) {
+                    volatile float diff = orc_half_to_float(wr[c]) - mn;
+                    volatile float ratio = diff / s;
+                    float rq = rintf(ratio);       /* default rounding mode: nearest even */
+                    if (rq < 0.0f) rq = 0.0f;
+                    if (rq > 255.0f) rq = 255.0f;
+                    q = (unsigned)rq;
+                }
+                qr[c] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
+static void dequant_row8(const uint8_t* qrow, const uint16_t* srow, const uint16_t* zrow, int in, uint16_t* out_row) {
+    for (int c = 0; c < in; ++c) {
+        float s = orc_half_to_float(srow[c / ORC_GROUP]);
+        float z = orc_half_to_float(zrow[c / ORC_GROUP]);
+        volatile float prod = (float)qrow[c] * s;
+        volatile float sum = prod + z;
+        out_row[c] = orc_float_to_half(sum);
+    }
+}
+
+int orc_dequant_int8(const uint8_t* q_bytes, const uint16_t* scale, const uint16_t* zero, int out, int in,
+                     uint16_t* w_hat) {
+    if (in % ORC_GROUP != 0 || out < 0) return -1;
+    const int groups = in / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < out; ++r)
+        dequant_row8(q_bytes + (size_t)r * in, scale + (size_t)r * groups, zero + (size_t)r * groups, in,
+                     w_hat + (size_t)r * in);
+    return 0;
+}
+
 /* ---------------------------------------------------------------- gating (§1, §2.1) */
 
 /*
@@ -254,8 +323,9 @@ int orc_permute(const int32_t* idx, int T, int k, int E, int32_t* counts, int32_
 
 /* ---------------------------------------------------------------- expert FFN (§1: experts are feed-forward layers) */
 
-/* One weight matrix [out,in]: 16-bit (data = fp16 [out,in], scale = zero = NULL)
- * or 4-bit (data = packed [out,in/2], scale/zero fp16 [out,in/64]). */
+/* One weight matrix [out,in]: 16-bit (data = fp16 [out,in], scale = zero = NULL), 4-bit (data = packed
+ * [out,in/2], scale/zero fp16 [out,in/64]) or 8-bit (data = bytes [out,in], scale/zero fp16 [out,in/64]).
+ * Precision codes used below: 0 = 16-bit, 1 = 4-bit, 2 = 8-bit. */
 typedef struct {
     const void* data;
     const uint16_t* scale;
@@ -266,10 +336,15 @@ typedef struct {
  * a 4-bit expert is by construction the 16-bit expert made of its dequantized weights. */
 static void mat_row(const orc_mat* m, int prec_int4, int r, int in, double* row, uint16_t* tmp) {
     const uint16_t* src;
-    if (prec_int4) {
+    if (prec_int4 == 1) {
         const int groups = in / ORC_GROUP;
         dequant_row((const uint8_t*)m->data + (size_t)r * (in / 2), m->scale + (size_t)r * groups,
                     m->zero + (size_t)r * groups, in, tmp);
+        src = tmp;
+    } else if (prec_int4 == 2) {
+        const int groups = in / ORC_GROUP;
+        dequant_row8((const uint8_t*)m->data + (size_t)r * in, m->scale + (size_t)r * groups,
+                     m->zero + (size_t)r * groups, in, tmp);
         src = tmp;
     } else {
         src = (const uint16_t*)m->data + (size_t)r * in;
@@ -332,7 +407,7 @@ int orc_expert_ffn(int prec_int4, const orc_mat* w1, const orc_mat* w3, const or
 /* ---------------------------------------------------------------- whole block */
 
 typedef struct {
-    int prec_int4;      /* the "quantized?" attribute of the paper's expert table (§3) */
+    int prec_int4;      /* the "quantized?" attribute of the paper's expert table (§3): 0 = 16-bit, 1 = 4-bit, 2 = 8-bit */
     int resident;       /* the location attribute (§3): 1 = in device memory */
     orc_mat w1, w3, w2;
 } orc_expert;
@@ -441,13 +516,13 @@ int orc_chain_layer(uint16_t* h, int T, int d, int f, int E, int k, const uint16
 static void mat_row_f32(const orc_mat* m, int prec_int4, int exact_weights, int r, int in, float* row) {
     if (prec_int4) {
         const int groups = in / ORC_GROUP;
-        const uint8_t* q = (const uint8_t*)m->data + (size_t)r * (in / 2);
+        const uint8_t* q = (const uint8_t*)m->data + (size_t)r * (prec_int4 == 2 ? in : in / 2);
         const uint16_t* sr = m->scale + (size_t)r * groups;
         const uint16_t* zr = m->zero + (size_t)r * groups;
         for (int c = 0; c < in; ++c) {
             float s = orc_half_to_float(sr[c / ORC_GROUP]);
             float z = orc_half_to_float(zr[c / ORC_GROUP]);
-            volatile float prod = (float)nibble_at(q, c) * s;
+            volatile float prod = (float)(prec_int4 == 2 ? (unsigned)q[c] : nibble_at(q, c)) * s;
             volatile float sum = prod + z;
             row[c] = exact_weights ? sum : orc_half_to_float(orc_float_to_half(sum));
         }

@@ -52,6 +52,8 @@ def lib():
         L.orc_double_to_half.restype = ctypes.c_uint16
         L.orc_quantize_int4.argtypes = [vp, i32, i32, vp, vp, vp]
         L.orc_dequant_int4.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.orc_quantize_int8.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.orc_dequant_int8.argtypes = [vp, vp, vp, i32, i32, vp]
         L.orc_route.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.orc_permute.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.orc_expert_ffn.argtypes = [i32, ctypes.POINTER(_Mat), ctypes.POINTER(_Mat), ctypes.POINTER(_Mat),
@@ -90,14 +92,29 @@ def _ptr(a: Optional[np.ndarray]):
 
 @dataclass
 class Mat:
-    """One weight matrix [out, in]: fp16 ``data`` or packed uint8 ``data`` [out, in/2] + fp16 ``scale``/``zero``."""
+    """One weight matrix [out, in]: fp16 ``data``; packed uint8 ``data`` [out, in/2] + fp16 ``scale``/``zero`` (4-bit);
+    or uint8 ``data`` [out, in] + fp16 ``scale``/``zero`` with ``bits`` = 8."""
     data: np.ndarray
     scale: Optional[np.ndarray] = None
     zero: Optional[np.ndarray] = None
+    bits: int = 4                      # of a quantized matrix (ignored when scale is None)
 
     @property
     def int4(self) -> bool:
-        return self.scale is not None
+        return self.scale is not None and self.bits == 4
+
+    @property
+    def int8(self) -> bool:
+        return self.scale is not None and self.bits == 8
+
+    @property
+    def prec(self) -> int:
+        """Precision code of the C oracle: 0 = 16-bit, 1 = 4-bit, 2 = 8-bit."""
+        return 0 if self.scale is None else (2 if self.bits == 8 else 1)
+
+    @property
+    def in_features(self) -> int:
+        return self.data.shape[1] * (2 if self.int4 else 1)
 
     def c(self) -> _Mat:
         return _Mat(_ptr(self.data), _ptr(self.scale), _ptr(self.zero))
@@ -114,8 +131,16 @@ class Expert:
     def int4(self) -> bool:
         return self.w1.int4
 
+    @property
+    def int8(self) -> bool:
+        return self.w1.int8
+
+    @property
+    def prec(self) -> int:
+        return self.w1.prec
+
     def c(self) -> _Expert:
-        return _Expert(int(self.int4), int(self.resident), self.w1.c(), self.w3.c(), self.w2.c())
+        return _Expert(self.prec, int(self.resident), self.w1.c(), self.w3.c(), self.w2.c())
 
 
 # ------------------------------------------------------------------ scalar helpers (for pins)
@@ -145,6 +170,28 @@ def quantize_int4(w: np.ndarray) -> Mat:
     if rc != 0:
         raise ValueError("orc_quantize_int4: shape not a multiple of the group size")
     return Mat(q, s, z)
+
+
+def quantize_int8(w: np.ndarray) -> Mat:
+    """fp16 [out,in] -> 8-bit Mat (asymmetric uint8, group 64 along ``in``, fp16 scale and zero)."""
+    w = _f16(w)
+    out, inn = w.shape
+    q = np.zeros((out, inn), dtype=np.uint8)
+    s = np.zeros((out, inn // GROUP), dtype=np.float16)
+    z = np.zeros((out, inn // GROUP), dtype=np.float16)
+    rc = lib().orc_quantize_int8(w.ctypes.data, out, inn, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    if rc != 0:
+        raise ValueError("orc_quantize_int8: shape not a multiple of the group size")
+    return Mat(q, s, z, bits=8)
+
+
+def dequant_int8(m: Mat) -> np.ndarray:
+    out, inn = m.data.shape
+    w = np.zeros((out, inn), dtype=np.float16)
+    rc = lib().orc_dequant_int8(m.data.ctypes.data, m.scale.ctypes.data, m.zero.ctypes.data, out, inn, w.ctypes.data)
+    if rc != 0:
+        raise ValueError("orc_dequant_int8: bad shape")
+    return w
 
 
 def dequant_int4(m: Mat) -> np.ndarray:
@@ -190,11 +237,11 @@ def permute(idx: np.ndarray, E: int):
 def expert_ffn(e: Expert, x_rows: np.ndarray, want_h: bool = False):
     x_rows = _f16(x_rows)
     n, d = x_rows.shape
-    f = e.w2.data.shape[1] * (2 if e.int4 else 1)
+    f = e.w2.in_features
     y = np.zeros((n, d), dtype=np.float64)
     h = np.zeros((n, f), dtype=np.float64) if want_h else None
     m1, m3, m2 = e.w1.c(), e.w3.c(), e.w2.c()
-    rc = lib().orc_expert_ffn(int(e.int4), ctypes.byref(m1), ctypes.byref(m3), ctypes.byref(m2), x_rows.ctypes.data,
+    rc = lib().orc_expert_ffn(e.prec, ctypes.byref(m1), ctypes.byref(m3), ctypes.byref(m2), x_rows.ctypes.data,
                               n, d, f, y.ctypes.data, _ptr(h))
     if rc != 0:
         raise ValueError("orc_expert_ffn: bad shape")
@@ -211,7 +258,7 @@ def _expert_array(experts: Sequence[Expert]):
 def _d_ff(experts: Sequence[Expert]) -> int:
     """d_ff read off the first expert that is resident (placeholders of absent experts carry no shape)."""
     e = next((x for x in experts if x.resident), experts[0])
-    return e.w2.data.shape[1] * (2 if e.int4 else 1)
+    return e.w2.in_features
 
 
 def layer_forward(x: np.ndarray, wg: np.ndarray, experts: Sequence[Expert], k: int,
@@ -280,11 +327,11 @@ def expert_ffn_f32(e: Expert, x_rows: np.ndarray, exact_weights: bool = False, w
     """The expert with fp32 accumulators and the hidden row rounded to fp16.  Returns y fp32 [n,d] (and h fp16)."""
     x_rows = _f16(x_rows)
     n, d = x_rows.shape
-    f = e.w2.data.shape[1] * (2 if e.int4 else 1)
+    f = e.w2.in_features
     y = np.zeros((n, d), dtype=np.float32)
     h = np.zeros((n, f), dtype=np.float16) if want_h else None
     m1, m3, m2 = e.w1.c(), e.w3.c(), e.w2.c()
-    rc = lib().orc_expert_ffn_f32(int(e.int4), ctypes.byref(m1), ctypes.byref(m3), ctypes.byref(m2),
+    rc = lib().orc_expert_ffn_f32(e.prec, ctypes.byref(m1), ctypes.byref(m3), ctypes.byref(m2),
                                   x_rows.ctypes.data, n, d, f, int(exact_weights), y.ctypes.data, _ptr(h))
     if rc != 0:
         raise ValueError("orc_expert_ffn_f32: bad shape")

@@ -55,8 +55,24 @@ int main(void) {
     ex[1].w3 = (orc_mat){q[1], sc[1], ze[1]};
     ex[1].w2 = (orc_mat){q[2], sc[2], ze[2]};
 
+    /* expert 2 becomes 8-bit */
+    uint8_t* q8[3] = {0, 0, 0};
+    uint16_t *sc8[3] = {0, 0, 0}, *ze8[3] = {0, 0, 0};
+    for (int m = 0; m < 3; ++m) {
+        q8[m] = (uint8_t*)malloc((size_t)outs[m] * ins[m]);
+        sc8[m] = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)outs[m] * ins[m] / ORC_GROUP);
+        ze8[m] = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)outs[m] * ins[m] / ORC_GROUP);
+        if (orc_quantize_int8(w[2][m], outs[m], ins[m], q8[m], sc8[m], ze8[m]) != 0) return 2;
+    }
+    ex[2].prec_int4 = 2;
+    ex[2].w1 = (orc_mat){q8[0], sc8[0], ze8[0]};
+    ex[2].w3 = (orc_mat){q8[1], sc8[1], ze8[1]};
+    ex[2].w2 = (orc_mat){q8[2], sc8[2], ze8[2]};
+
     double sum = 0.0;
     uint16_t* w_hat = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)F * D);
+    if (orc_dequant_int8(q8[0], sc8[0], ze8[0], F, D, w_hat) != 0) return 3;
+    for (size_t i = 0; i < (size_t)F * D; ++i) sum += orc_half_to_float(w_hat[i]);
     if (orc_dequant_int4(q[0], sc[0], ze[0], F, D, w_hat) != 0) return 3;
     for (size_t i = 0; i < (size_t)F * D; ++i) sum += orc_half_to_float(w_hat[i]);
 
@@ -88,6 +104,20 @@ int main(void) {
         if (orc_chain_layer(hh, T, D, F, E, K, gain, 1e-5, wg, NULL, ex, idx, gate, normed) != 0) return 8;
     for (size_t i = 0; i < (size_t)T * D; ++i) sum += orc_half_to_float(hh[i]);
 
+    /* the second mode (fp32 accumulators, fp16 intermediates), every precision */
+    float* y32 = (float*)malloc(sizeof(float) * (size_t)T * D);
+    uint16_t* h16 = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * F);
+    for (int e = 0; e < E; ++e) {
+        if (orc_expert_ffn_f32(ex[e].prec_int4, &ex[e].w1, &ex[e].w3, &ex[e].w2, x, T, D, F, e & 1, y32, h16) != 0) return 10;
+        for (size_t i = 0; i < (size_t)T * D; ++i) sum += y32[i];
+    }
+    uint16_t* out16 = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * D);
+    if (orc_layer_forward_f32(x, T, D, F, E, K, wg, bias, ex, 1, x, out16, idx, gate) != 0) return 11;
+    memcpy(hh, x, sizeof(uint16_t) * (size_t)T * D);
+    if (orc_chain_layer_f32(hh, T, D, F, E, K, gain, 1e-5f, wg, NULL, ex, 0, idx, gate) != 0) return 12;
+    for (size_t i = 0; i < (size_t)T * D; ++i) sum += orc_half_to_float(out16[i]) + orc_half_to_float(hh[i]);
+    free(y32); free(h16); free(out16);
+
     /* a routed expert that is not resident must be reported, not read */
     ex[idx[0]].resident = 0;
     memcpy(hh, x, sizeof(uint16_t) * (size_t)T * D);
@@ -97,7 +127,7 @@ int main(void) {
     printf("checksum %.6f threads %d\n", sum, orc_max_threads());
     free(x); free(wg); free(w_hat); free(idx); free(gate); free(logits); free(perm); free(y); free(h); free(out);
     free(gain); free(normed); free(hh);
-    for (int m = 0; m < 3; ++m) { free(q[m]); free(sc[m]); free(ze[m]); }
+    for (int m = 0; m < 3; ++m) { free(q[m]); free(sc[m]); free(ze[m]); free(q8[m]); free(sc8[m]); free(ze8[m]); }
     for (int e = 0; e < E; ++e) for (int m = 0; m < 3; ++m) free(w[e][m]);
     return 0;
 }

@@ -11,6 +11,7 @@ GOLDEN = Path(__file__).resolve().parent / "golden" / "paper_constants.txt"
 D_MODEL, D_FF = 4096, 14336                       # Mixtral 8x7B expert shape (§4.1)
 E16_BYTES = 3 * D_MODEL * D_FF * 2                # three fp16 matrices
 E4_BYTES = 3 * (D_MODEL * D_FF // 2 + 2 * (D_MODEL * D_FF // 64) * 2)     # codes + fp16 scale and zero per 64
+E8_BYTES = 3 * (D_MODEL * D_FF + 2 * (D_MODEL * D_FF // 64) * 2)          # one code per byte + the same scales
 
 
 @pytest.fixture(scope="module")
@@ -46,6 +47,11 @@ def test_table1_sizes_follow_from_the_parts(paper):
     ours = paper["non_expert_size_GB"] * 1e9 + paper["total_experts"] * E4_BYTES
     assert paper["model_size_mixed_min_GB"] < ours / 1e9 < 1.1 * paper["model_size_mixed_min_GB"]
     assert E4_BYTES * 16 / E16_BYTES == 4.5
+    # Table 1's homogeneous 8-bit row is half the 16-bit model; this library's 8-bit form takes 8.5 bits per weight
+    assert E8_BYTES * 16 / E16_BYTES == 8.5 and E8_BYTES == 187_170_816
+    ours8 = paper["non_expert_size_GB"] * 1e9 + paper["total_experts"] * E8_BYTES
+    assert abs(ours8 / 1e9 - (paper["non_expert_size_GB"] + (paper["model_size_8bit_GB"] - paper["non_expert_size_GB"] / 2)
+                              * 8.5 / 8)) < 0.03 * paper["model_size_8bit_GB"]
 
 
 def test_expert_copy_time_is_a_pcie_gen4_rate(paper):
