@@ -33,6 +33,9 @@
  *     weight: the multi-token kernels with one fp16 multiply-add (a single rounding), the one-token kernels
  *     in the factored form scale * sum(code * x) + zero * sum(x) in fp32 (no rounding of the weight); both
  *     stay within the tolerance stated for the block outputs, not bit-exact per weight.
+ *   - 8-bit (the precision of the paper's homogeneous 8-bit comparison model, §4 Table 1) follows the same scheme:
+ *     asymmetric uint8, groups of 64 columns with an fp16 scale and an fp16 zero, one code per byte;
+ *     dequantized weight = fp16_rne( fp32(code) * fp32(scale) + fp32(zero) ).
  *   - d_model and d_ff must be multiples of 64, d_model <= 8192, d_ff <= 16384 (else MOE_ESHAPE);
  *     n_experts <= MOE_MAX_EXPERTS; 1 <= top_k <= min(n_experts, MOE_MAX_TOPK).
  */
@@ -61,11 +64,11 @@ typedef enum {
 } moe_status;
 
 /* The "quantized?" attribute of the paper's expert table (§3). */
-typedef enum { MOE_PREC_FP16 = 0, MOE_PREC_INT4G64 = 1 } moe_prec;
+typedef enum { MOE_PREC_FP16 = 0, MOE_PREC_INT4G64 = 1, MOE_PREC_INT8G64 = 2 } moe_prec;
 
 /* One weight matrix [out, in] in device memory. */
 typedef struct {
-    const void* data;  /* device: fp16 [out,in], or uint8 [out,in/2] of packed codes */
+    const void* data;  /* device: fp16 [out,in]; uint8 [out,in/2] of packed 4-bit codes; or uint8 [out,in] of 8-bit codes */
     const void* scale; /* device: fp16 [out,in/64]; NULL for a 16-bit matrix */
     const void* zero;  /* device: fp16 [out,in/64]; NULL for a 16-bit matrix */
 } moe_mat;
@@ -219,6 +222,14 @@ int moe_dequant_int4(const moe_mat* m, int out, int in, void* w_fp16, moe_stream
  */
 int moe_quantize_int4(const void* w_fp16, int out, int in, void* packed, void* scale, void* zero,
                       moe_stream_t stream);
+
+/*
+ * The same two hooks for the 8-bit form: codes: device uint8 [out,in]; scale, zero: device fp16 [out,in/64];
+ * scale = fp16_rne((fp32(max) - fp32(min)) / 255), code = clamp(rint((fp32(w) - fp32(zero)) / fp32(scale)), 0, 255).
+ * Both are bit-exact against the definition.
+ */
+int moe_dequant_int8(const moe_mat* m, int out, int in, void* w_fp16, moe_stream_t stream);
+int moe_quantize_int8(const void* w_fp16, int out, int in, void* codes, void* scale, void* zero, moe_stream_t stream);
 
 /*
  * Seeded synthetic tensors written directly in device memory (stand-ins for trained weights and real

@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence
 _LIB_PATH = Path(__file__).resolve().parent / "libmoemix.so"
 
 MOE_OK, MOE_EINVAL, MOE_ESHAPE, MOE_ENOTRESIDENT, MOE_EWORKSPACE, MOE_EHIP = 0, -1, -2, -3, -4, -5
-PREC_FP16, PREC_INT4G64 = 0, 1
+PREC_FP16, PREC_INT4G64, PREC_INT8G64 = 0, 1, 2
 GROUP = 64
 STATUS_BAD_INDEX = 1 << 1
 STATUS_NOT_RESIDENT = 1 << 3
@@ -25,6 +25,7 @@ EXPORTS = (
     "moe_chain_forward", "moe_dequant_int4", "moe_quantize_int4", "moe_synth_fill_f16", "moe_read_status",
     "moe_last_error", "moe_version", "moe_trace_kernel", "moe_plan", "moe_swap_slot_bytes", "moe_layer_forward_swap",
     "moe_stream_read", "moe_static_scratch_bytes", "moe_layer_forward_static",
+    "moe_dequant_int8", "moe_quantize_int8",
 )
 
 
@@ -91,6 +92,8 @@ def lib():
         L.moe_chain_forward.argtypes = [LP, ctypes.POINTER(vp), i32, ctypes.c_float, vp, i32, vp, vp, sz, vp]
         L.moe_dequant_int4.argtypes = [ctypes.POINTER(CMat), i32, i32, vp, vp]
         L.moe_quantize_int4.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.moe_dequant_int8.argtypes = [ctypes.POINTER(CMat), i32, i32, vp, vp]
+        L.moe_quantize_int8.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.moe_synth_fill_f16.argtypes = [vp, sz, sz, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_float, i32, vp]
         L.moe_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int)]
         L.moe_trace_kernel.argtypes = [i32, vp, vp]
@@ -270,6 +273,16 @@ def moe_quantize_int4(w_fp16, packed, scale, zero) -> None:
     _check(lib().moe_quantize_int4(_ptr(w_fp16), out, inn, _ptr(packed), _ptr(scale), _ptr(zero), _stream()))
 
 
+def moe_dequant_int8(m: Mat, out: int, inn: int, w_fp16) -> None:
+    cm = m.c()
+    _check(lib().moe_dequant_int8(ctypes.byref(cm), out, inn, _ptr(w_fp16), _stream()))
+
+
+def moe_quantize_int8(w_fp16, codes, scale, zero) -> None:
+    out, inn = w_fp16.shape
+    _check(lib().moe_quantize_int8(_ptr(w_fp16), out, inn, _ptr(codes), _ptr(scale), _ptr(zero), _stream()))
+
+
 def moe_synth_fill_f16(dst, first: int, seed: int, stream_id: int, scale: float, kind: int) -> None:
     _check(lib().moe_synth_fill_f16(_ptr(dst), dst.numel(), first, seed, stream_id, scale, kind, _stream()))
 
@@ -321,3 +334,14 @@ def quantize_mat(w_fp16) -> Mat:
     zero = torch.empty((out, inn // GROUP), dtype=torch.float16, device=w_fp16.device)
     moe_quantize_int4(w_fp16, packed, scale, zero)
     return Mat(packed, scale, zero)
+
+
+def quantize_mat8(w_fp16) -> Mat:
+    """Device-side 16-bit -> 8-bit switch of one matrix (moe_quantize_int8)."""
+    import torch
+    out, inn = w_fp16.shape
+    codes = torch.empty((out, inn), dtype=torch.uint8, device=w_fp16.device)
+    scale = torch.empty((out, inn // GROUP), dtype=torch.float16, device=w_fp16.device)
+    zero = torch.empty((out, inn // GROUP), dtype=torch.float16, device=w_fp16.device)
+    moe_quantize_int8(w_fp16, codes, scale, zero)
+    return Mat(codes, scale, zero)

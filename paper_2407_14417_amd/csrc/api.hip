@@ -43,11 +43,11 @@ int check_layer(const moe_layer* L) {
         return fail(MOE_ESHAPE, "top_k=%d outside [1, min(n_experts, %d)]", L->top_k, MOE_MAX_TOPK);
     for (int e = 0; e < L->n_experts; ++e) {
         const moe_expert& x = L->experts[e];
-        if (x.prec != MOE_PREC_FP16 && x.prec != MOE_PREC_INT4G64)
+        if (x.prec != MOE_PREC_FP16 && x.prec != MOE_PREC_INT4G64 && x.prec != MOE_PREC_INT8G64)
             return fail(MOE_EINVAL, "expert %d: unknown precision %d", e, x.prec);
-        if (x.resident && x.prec == MOE_PREC_INT4G64 &&
+        if (x.resident && x.prec != MOE_PREC_FP16 &&
             (!x.w1.scale || !x.w1.zero || !x.w3.scale || !x.w3.zero || !x.w2.scale || !x.w2.zero))
-            return fail(MOE_EINVAL, "expert %d: 4-bit matrices need scale and zero", e);
+            return fail(MOE_EINVAL, "expert %d: quantized matrices need scale and zero", e);
     }
     return MOE_OK;
 }
@@ -58,7 +58,15 @@ constexpr int kDecodeUpBlocks = 1024;
 
 // Which kernels serve T tokens of a block: T == 1 the batch-1 kernels, otherwise the matrix-core path when
 // the shape allows it, else the shape-agnostic kernels.
-bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff); }
+// 8-bit experts run on the shape-agnostic kernels: a block that holds one anywhere takes those for every expert
+// (which expert a token meets is only known on the device).
+bool has_int8(const moe_layer* L) {
+    for (int e = 0; e < L->n_experts; ++e)
+        if (L->experts[e].prec == MOE_PREC_INT8G64) return true;
+    return false;
+}
+bool use_decode(const moe_layer* L, int T) { return T == 1 && decode_shape_ok(L->d_model, L->d_ff) && !has_int8(L); }
+bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff) && !has_int8(L); }
 
 MfmaPlan plan_for(const moe_layer* L, int rows) { return plan_mfma(rows, L->d_model, L->d_ff, L->n_experts); }
 
@@ -100,7 +108,7 @@ int layer_body(const moe_layer* L, const DevExperts& table, const half_t* x, int
                const half_t* residual, half_t* out, int32_t* idx_out, float* gate_out, const Workspace& w,
                bool reset_status, hipStream_t st) {
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
-    if (T == 1 && decode_shape_ok(d, f)) {
+    if (use_decode(L, T)) {
         // batch-1 decode: two launches.  The gating network (and the RMSNorm of the chain) runs inside the
         // up-projection launch, no grouping is needed, the weighted average is fused into the down-projection.
         // The up-projection launch clears the word it is given: the status word for the first block of a call, a
@@ -214,7 +222,7 @@ int moe_expert_ffn_mixed(const moe_layer* layer, int expert, const void* x_rows,
     RowMap rows{nullptr, nullptr, layer->top_k, expert, n};
     const int d = layer->d_model, f = layer->d_ff;
     launch_zero_words(w.status, 1, st);   // the status word describes this call
-    if (n == 1 && decode_shape_ok(d, f)) {
+    if (use_decode(layer, n)) {
         // one row: the batch-1 kernels, with the routing result "this expert, weight 1" written to the workspace
         launch_single_route(w.idx, w.gate, expert, st);
         launch_decode_up(table, w.idx, (const half_t*)x_rows, d, f, 1, w.h, w.status, kDecodeUpBlocks, st);
@@ -319,9 +327,9 @@ struct MatBytes {
     size_t total() const { return align256(data) + align256(scale) + align256(zero); }
 };
 MatBytes mat_bytes(int prec, int out, int in) {
-    if (prec == MOE_PREC_INT4G64) {
+    if (prec == MOE_PREC_INT4G64 || prec == MOE_PREC_INT8G64) {
         const size_t g = (size_t)out * (in / MOE_GROUP) * 2;
-        return MatBytes{(size_t)out * in / 2, g, g};
+        return MatBytes{prec == MOE_PREC_INT4G64 ? (size_t)out * in / 2 : (size_t)out * in, g, g};
     }
     return MatBytes{(size_t)out * in * 2, 0, 0};
 }
@@ -347,7 +355,7 @@ hipError_t copy_mat(const moe_mat& src, const MatBytes& b, char*& cursor, DevMat
 void run_experts(const moe_layer* L, const DevExperts& table, const half_t* x, int T, const Workspace& w,
                  const half_t* decode_residual, half_t* out, hipStream_t st) {
     const int d = L->d_model, f = L->d_ff, E = L->n_experts, k = L->top_k;
-    if (T == 1 && decode_shape_ok(d, f)) {
+    if (use_decode(L, T)) {
         launch_decode_up(table, w.idx, x, d, f, k, w.h, w.status, kDecodeUpBlocks, st);
         launch_decode_down(table, w.idx, w.gate, w.h, d, f, k, decode_residual, out, w.status, st);
         return;
@@ -410,9 +418,9 @@ int moe_layer_forward_swap(const moe_layer* layer, const moe_swap* swap, const v
         seen |= 1u << ex;
         const moe_expert& he = swap->host_experts[ex];
         if (expert_resident(layer->experts[ex]) || !he.w1.data || !he.w3.data || !he.w2.data) continue;
-        if (layer->experts[ex].prec == MOE_PREC_INT4G64 &&
+        if (layer->experts[ex].prec != MOE_PREC_FP16 &&
             (!he.w1.scale || !he.w1.zero || !he.w3.scale || !he.w3.zero || !he.w2.scale || !he.w2.zero))
-            return fail(MOE_EINVAL, "host expert %d: 4-bit matrices need scale and zero", ex);
+            return fail(MOE_EINVAL, "host expert %d: quantized matrices need scale and zero", ex);
         missed[n_miss++] = ex;
     }
     if (n_missed) *n_missed = n_miss;
@@ -420,7 +428,7 @@ int moe_layer_forward_swap(const moe_layer* layer, const moe_swap* swap, const v
     // pass over the resident experts; the missed ones wait for their copies
     DevExperts table = device_table(layer);
     for (int i = 0; i < n_miss; ++i) table.e[missed[i]].resident = kDeferred;
-    const bool decode = T == 1 && decode_shape_ok(d, f);
+    const bool decode = use_decode(layer, T);
     if (!decode) launch_permute(w.idx, T * k, E, w.counts, w.offsets, w.perm, w.inv, w.status, st);
     run_experts(layer, table, xin, T, w, nullptr, (half_t*)out, st);
 
@@ -500,6 +508,24 @@ int moe_quantize_int4(const void* w_fp16, int out, int in, void* packed, void* s
     if (out < 0 || in < 0) return fail(MOE_EINVAL, "moe_quantize_int4: negative size");
     if (in % MOE_GROUP) return fail(MOE_ESHAPE, "moe_quantize_int4: in=%d not a multiple of %d", in, MOE_GROUP);
     launch_quantize_int4((const half_t*)w_fp16, out, in, (uint8_t*)packed, (half_t*)scale, (half_t*)zero,
+                         (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_dequant_int8(const moe_mat* m, int out, int in, void* w_fp16, moe_stream_t stream) {
+    if (!m || !m->data || !m->scale || !m->zero || !w_fp16) return fail(MOE_EINVAL, "moe_dequant_int8: NULL argument");
+    if (out < 0 || in < 0) return fail(MOE_EINVAL, "moe_dequant_int8: negative size");
+    if (in % MOE_GROUP) return fail(MOE_ESHAPE, "moe_dequant_int8: in=%d not a multiple of %d", in, MOE_GROUP);
+    launch_dequant_int8(DevMat{(const uint8_t*)m->data, (const half_t*)m->scale, (const half_t*)m->zero}, out, in,
+                        (half_t*)w_fp16, (hipStream_t)stream);
+    return check_hip((hipStream_t)stream);
+}
+
+int moe_quantize_int8(const void* w_fp16, int out, int in, void* codes, void* scale, void* zero, moe_stream_t stream) {
+    if (!w_fp16 || !codes || !scale || !zero) return fail(MOE_EINVAL, "moe_quantize_int8: NULL argument");
+    if (out < 0 || in < 0) return fail(MOE_EINVAL, "moe_quantize_int8: negative size");
+    if (in % MOE_GROUP) return fail(MOE_ESHAPE, "moe_quantize_int8: in=%d not a multiple of %d", in, MOE_GROUP);
+    launch_quantize_int8((const half_t*)w_fp16, out, in, (uint8_t*)codes, (half_t*)scale, (half_t*)zero,
                          (hipStream_t)stream);
     return check_hip((hipStream_t)stream);
 }

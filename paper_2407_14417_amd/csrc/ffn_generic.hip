@@ -70,6 +70,31 @@ __device__ __forceinline__ void row_dot_int4(const uint8_t* __restrict__ qrow, c
     }
 }
 
+// 8-bit rows: a lane's 128-bit load holds 16 codes, all of one group of 64 columns.
+template <int NT>
+__device__ __forceinline__ void row_dot_int8(const uint8_t* __restrict__ qrow, const half_t* __restrict__ srow,
+                                             const half_t* __restrict__ zrow, const half_t* __restrict__ act, int K,
+                                             int nt, int lane, float (&acc)[NT]) {
+    for (int c = lane * 16; c < K; c += kWave * 16) {
+        const uint4_t pk = *(const uint4_t*)(qrow + c);
+        const float s = (float)srow[c >> 6], z = (float)zrow[c >> 6];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            half4_t wv;
+#pragma unroll
+            for (int n = 0; n < 4; ++n) wv[n] = dequant_one((pk[j] >> (8 * n)) & 0xFFu, s, z);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                if (t < nt) {
+                    const half4_t xv = *(const half4_t*)(act + (size_t)t * K + c + j * 4);
+#pragma unroll
+                    for (int n = 0; n < 4; ++n) acc[t] += (float)wv[n] * (float)xv[n];
+                }
+            }
+        }
+    }
+}
+
 template <int NT>
 __global__ __launch_bounds__(256) void ffn_up_generic(DevExperts ex, RowMap rows, const half_t* __restrict__ x, int d,
                                                        int f, half_t* __restrict__ h, int32_t* status) {
@@ -83,7 +108,7 @@ __global__ __launch_bounds__(256) void ffn_up_generic(DevExperts ex, RowMap rows
         if (tid == 0 && blockIdx.x == 0) atomicOr(status, kStatusNotResident);
         return;
     }
-    const bool int4 = ee.prec == MOE_PREC_INT4G64;
+    const bool int4 = ee.prec == MOE_PREC_INT4G64, int8 = ee.prec == MOE_PREC_INT8G64;
     const int row0 = blockIdx.x * kRowsPerBlock;
     for (int rc = sp.begin; rc < sp.end; rc += NT) {
         const int nt = min(NT, sp.end - rc);
@@ -105,6 +130,12 @@ __global__ __launch_bounds__(256) void ffn_up_generic(DevExperts ex, RowMap rows
                 row_dot_int4<NT>(ee.w1.data + (size_t)row * (d >> 1), ee.w1.scale + (size_t)row * gpr,
                                  ee.w1.zero + (size_t)row * gpr, act, d, nt, lane, a);
                 row_dot_int4<NT>(ee.w3.data + (size_t)row * (d >> 1), ee.w3.scale + (size_t)row * gpr,
+                                 ee.w3.zero + (size_t)row * gpr, act, d, nt, lane, b);
+            } else if (int8) {
+                const int gpr = d >> 6;
+                row_dot_int8<NT>(ee.w1.data + (size_t)row * d, ee.w1.scale + (size_t)row * gpr,
+                                 ee.w1.zero + (size_t)row * gpr, act, d, nt, lane, a);
+                row_dot_int8<NT>(ee.w3.data + (size_t)row * d, ee.w3.scale + (size_t)row * gpr,
                                  ee.w3.zero + (size_t)row * gpr, act, d, nt, lane, b);
             } else {
                 row_dot_fp16<NT>((const half_t*)ee.w1.data + (size_t)row * d, act, d, nt, lane, a);
@@ -138,7 +169,7 @@ __global__ __launch_bounds__(256) void ffn_down_generic(DevExperts ex, RowMap ro
                 y[(size_t)r * d + c] = 0.0f;
         return;
     }
-    const bool int4 = ee.prec == MOE_PREC_INT4G64;
+    const bool int4 = ee.prec == MOE_PREC_INT4G64, int8 = ee.prec == MOE_PREC_INT8G64;
     const int row0 = blockIdx.x * kRowsPerBlock;
     for (int rc = sp.begin; rc < sp.end; rc += NT) {
         const int nt = min(NT, sp.end - rc);
@@ -156,6 +187,10 @@ __global__ __launch_bounds__(256) void ffn_down_generic(DevExperts ex, RowMap ro
             if (int4) {
                 const int gpr = f >> 6;
                 row_dot_int4<NT>(ee.w2.data + (size_t)row * (f >> 1), ee.w2.scale + (size_t)row * gpr,
+                                 ee.w2.zero + (size_t)row * gpr, act, f, nt, lane, a);
+            } else if (int8) {
+                const int gpr = f >> 6;
+                row_dot_int8<NT>(ee.w2.data + (size_t)row * f, ee.w2.scale + (size_t)row * gpr,
                                  ee.w2.zero + (size_t)row * gpr, act, f, nt, lane, a);
             } else {
                 row_dot_fp16<NT>((const half_t*)ee.w2.data + (size_t)row * f, act, f, nt, lane, a);

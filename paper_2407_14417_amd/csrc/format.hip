@@ -65,6 +65,62 @@ void launch_quantize_int4(const half_t* w, int out, int in, uint8_t* packed, hal
     quantize_int4_kernel<<<(unsigned)((n_groups + 3) / 4), 256, 0, st>>>(w, n_groups, packed, scale, zero);
 }
 
+// 8-bit form: one thread per 4 weights (one 32-bit word of codes).
+__global__ __launch_bounds__(256) void dequant_int8_kernel(DevMat m, size_t n_words, int in, half_t* __restrict__ w) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_words) return;
+    const size_t col0 = (i * 4) % (size_t)in, row = (i * 4) / (size_t)in;
+    const size_t g = row * (size_t)(in >> 6) + (col0 >> 6);
+    const float s = (float)m.scale[g], z = (float)m.zero[g];
+    const uint32_t word = ((const uint32_t*)m.data)[i];
+    half4_t o;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) o[n] = dequant_one((word >> (8 * n)) & 0xFFu, s, z);
+    *(half4_t*)(w + i * 4) = o;
+}
+
+void launch_dequant_int8(const DevMat& m, int out, int in, half_t* w, hipStream_t st) {
+    const size_t n_words = (size_t)out * in / 4;
+    if (n_words == 0) return;
+    dequant_int8_kernel<<<(unsigned)((n_words + 255) / 256), 256, 0, st>>>(m, n_words, in, w);
+}
+
+// One wavefront per group of 64 weights, as in the 4-bit quantizer; one code per byte.
+__global__ __launch_bounds__(256) void quantize_int8_kernel(const half_t* __restrict__ w, size_t n_groups,
+                                                             uint8_t* __restrict__ codes, half_t* __restrict__ scale,
+                                                             half_t* __restrict__ zero) {
+    const size_t g = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= n_groups) return;
+    const int lane = threadIdx.x & 63;
+    const float v = (float)w[g * 64 + lane];
+    float mn = v, mx = v;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, m, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
+    }
+    const float range = __fsub_rn(mx, mn);
+    const half_t s16 = f32_to_f16_rne(__fdiv_rn(range, 255.0f));
+    const float s = (float)s16;
+    uint32_t q = 0;
+    if (s != 0.0f) {
+        float r = rintf(__fdiv_rn(__fsub_rn(v, mn), s));
+        r = fminf(fmaxf(r, 0.0f), 255.0f);
+        q = (uint32_t)r;
+    }
+    codes[g * 64 + lane] = (uint8_t)q;
+    if (lane == 0) {
+        scale[g] = s16;
+        zero[g] = (half_t)mn;
+    }
+}
+
+void launch_quantize_int8(const half_t* w, int out, int in, uint8_t* codes, half_t* scale, half_t* zero, hipStream_t st) {
+    const size_t n_groups = (size_t)out * in / 64;
+    if (n_groups == 0) return;
+    quantize_int8_kernel<<<(unsigned)((n_groups + 3) / 4), 256, 0, st>>>(w, n_groups, codes, scale, zero);
+}
+
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     z += 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;

@@ -84,6 +84,8 @@ void launch_quantize_int4(const half_t* w, int out, int in, uint8_t* packed, hal
                           hipStream_t st);
 // Reads `bytes` (a multiple of 16) of device memory once with streamed 128-bit loads.
 void launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t st);
+void launch_dequant_int8(const DevMat& m, int out, int in, half_t* w, hipStream_t st);
+void launch_quantize_int8(const half_t* w, int out, int in, uint8_t* codes, half_t* scale, half_t* zero, hipStream_t st);
 void launch_synth_fill(half_t* dst, size_t n, size_t first, uint64_t seed, uint64_t stream_id, float scale, int kind,
                        hipStream_t st);
 

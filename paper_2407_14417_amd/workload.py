@@ -29,22 +29,24 @@ def fill_uniform(shape, a: float, seed: int, stream_id: int, first: int = 0) -> 
     return t
 
 
-def device_expert(d: int, f: int, seed: int, layer: int, expert: int, int4: bool) -> mm.Expert:
-    """Expert ``expert`` of ``layer``: w1, w3 [f,d], w2 [d,f] ~ N(0, 0.02), 16-bit or quantized to 4-bit."""
+def device_expert(d: int, f: int, seed: int, layer: int, expert: int, int4: bool, int8: bool = False) -> mm.Expert:
+    """Expert ``expert`` of ``layer``: w1, w3 [f,d], w2 [d,f] ~ N(0, 0.02), 16-bit or quantized to 4 or 8 bits."""
     mats = []
     for which, shape in enumerate(((f, d), (f, d), (d, f))):
         w = fill_normal(shape, SIGMA_W, seed, synth.expert_stream(layer, expert, which))
-        if int4:
-            m = mm.quantize_mat(w)
+        if int4 or int8:
+            m = mm.quantize_mat(w) if int4 else mm.quantize_mat8(w)
             del w
         else:
             m = mm.Mat(w)
         mats.append(m)
-    return mm.Expert(mm.PREC_INT4G64 if int4 else mm.PREC_FP16, mats[0], mats[1], mats[2])
+    prec = mm.PREC_INT4G64 if int4 else (mm.PREC_INT8G64 if int8 else mm.PREC_FP16)
+    return mm.Expert(prec, mats[0], mats[1], mats[2])
 
 
 def device_layer(d: int, f: int, n_experts: int, top_k: int, int4_experts: Sequence[int], seed: int = 0,
-                 layer: int = 0, router: str = "normal", zipf: Optional[float] = None) -> mm.Layer:
+                 layer: int = 0, router: str = "normal", zipf: Optional[float] = None,
+                 int8_experts: Sequence[int] = ()) -> mm.Layer:
     """One synthetic MoE block in device memory.  ``router``: "normal" = N(0, 0.02) gate matrix,
     "uniform" = U(+-0.02*sqrt(3)); ``zipf``: exponent of the per-expert logit offsets ln p_e, p_e ~ (e+1)^-s."""
     stream = synth.STREAM_WG + 16 * layer
@@ -53,7 +55,8 @@ def device_layer(d: int, f: int, n_experts: int, top_k: int, int4_experts: Seque
     else:
         wg = fill_normal((n_experts, d), SIGMA_W, seed, stream)
     bias = None if zipf is None else torch.from_numpy(synth.zipf_bias(n_experts, zipf)).cuda()
-    experts = [device_expert(d, f, seed, layer, e, e in set(int4_experts)) for e in range(n_experts)]
+    experts = [device_expert(d, f, seed, layer, e, e in set(int4_experts), e in set(int8_experts))
+               for e in range(n_experts)]
     return mm.Layer(d, f, top_k, wg, experts, bias)
 
 

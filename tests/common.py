@@ -95,6 +95,7 @@ class Config:
     router: str = "normal"          # "normal": Wg ~ N(0, 0.02); "uniform": Wg ~ U(+-0.02*sqrt(3))
     zipf: Optional[float] = None    # exponent of the per-expert logit offsets, None = no bias
     layer: int = 0
+    int8_experts: tuple = ()        # experts held in the 8-bit form
 
 
 TINY = Config("tiny", 256, 512, 4, 2, 16, (1, 3))
@@ -182,6 +183,8 @@ def build_workload(cfg: Config, orc, experts_needed=None) -> Workload:
         w1, w3, w2 = expert_weights_f16(cfg, e)
         if e in cfg.int4_experts:
             experts.append(orc.Expert(orc.quantize_int4(w1), orc.quantize_int4(w3), orc.quantize_int4(w2)))
+        elif e in cfg.int8_experts:
+            experts.append(orc.Expert(orc.quantize_int8(w1), orc.quantize_int8(w3), orc.quantize_int8(w2)))
         else:
             experts.append(orc.Expert(orc.Mat(w1), orc.Mat(w3), orc.Mat(w2)))
     return Workload(cfg, x, wg, bias, experts)

@@ -11,6 +11,11 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def prec_of(e) -> int:
+    """Library precision code of an oracle expert."""
+    return mm.PREC_INT4G64 if e.int4 else (mm.PREC_INT8G64 if e.int8 else mm.PREC_FP16)
+
+
 def device_mat(m) -> mm.Mat:
     if m.scale is None:
         return mm.Mat(dev(m.data))
@@ -20,8 +25,7 @@ def device_mat(m) -> mm.Mat:
 def device_expert(e) -> mm.Expert:
     if e is None:
         return mm.Expert(mm.PREC_FP16, None, None, None, resident=False)
-    return mm.Expert(mm.PREC_INT4G64 if e.int4 else mm.PREC_FP16, device_mat(e.w1), device_mat(e.w3),
-                     device_mat(e.w2), resident=e.resident)
+    return mm.Expert(prec_of(e), device_mat(e.w1), device_mat(e.w3), device_mat(e.w2), resident=e.resident)
 
 
 def device_layer(wl) -> mm.Layer:
@@ -40,7 +44,7 @@ def host_expert(e) -> mm.Expert:
         if m.scale is None:
             return mm.Mat(pinned(m.data))
         return mm.Mat(pinned(m.data), pinned(m.scale), pinned(m.zero))
-    return mm.Expert(mm.PREC_INT4G64 if e.int4 else mm.PREC_FP16, mat(e.w1), mat(e.w3), mat(e.w2), resident=False)
+    return mm.Expert(prec_of(e), mat(e.w1), mat(e.w3), mat(e.w2), resident=False)
 
 
 def device_layer_with_offloaded(wl, offloaded):
@@ -50,7 +54,7 @@ def device_layer_with_offloaded(wl, offloaded):
     experts, hosts = [], []
     for i, e in enumerate(wl.experts):
         if i in offloaded:
-            experts.append(mm.Expert(mm.PREC_INT4G64 if e.int4 else mm.PREC_FP16, None, None, None, resident=False))
+            experts.append(mm.Expert(prec_of(e), None, None, None, resident=False))
             hosts.append(host_expert(e))
         else:
             experts.append(device_expert(e))
