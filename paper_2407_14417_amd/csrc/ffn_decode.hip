@@ -98,6 +98,43 @@ __device__ __forceinline__ float dot_i4(const uint4_t pk, const ActI4& a, float 
     return fmaf(s, t, z * a.c2);
 }
 
+// 8-bit layout.  A lane's 128-bit load holds 16 consecutive codes, all of one group of 64 columns.  A byte
+// permute puts each code into the mantissa of fp16 1024.0 (0x64 in the high byte), in natural column pairs.
+struct ActI8 {
+    half2_t p[8];   // the lane's 16 activations of one 1024-column chunk, natural pairs
+    float k1;       // 1024 * (sum of the 16 x): offset of the biased codes
+    float sx;       // sum of the 16 x: multiplies the group zero
+};
+
+__device__ __forceinline__ void load_act_i8(const half_t* __restrict__ src, ActI8& a) {
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const half8_t v = *(const half8_t*)(src + 8 * j);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a.p[4 * j + q] = half2_t{v[2 * q], v[2 * q + 1]};
+        sum += (((float)v[0] + (float)v[1]) + ((float)v[2] + (float)v[3])) +
+               (((float)v[4] + (float)v[5]) + ((float)v[6] + (float)v[7]));
+    }
+    a.sx = sum;
+    a.k1 = 1024.0f * sum;
+}
+
+// s * sum_c q_c x_c + z * sum_c x_c over the lane's 16 columns of one row.
+__device__ __forceinline__ float dot_i8(const uint4_t pk, const ActI8& a, float s, float z) {
+    uint32_t magic;
+    asm("v_mov_b32 %0, 0x64646464" : "=v"(magic));   // not volatile: identical copies are merged and hoisted
+    float lo = 0.0f, hi = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const half2_t q01 = as_half2(__builtin_amdgcn_perm(magic, pk[j], 0x04010400u));    // (1024 + q0, 1024 + q1)
+        const half2_t q23 = as_half2(__builtin_amdgcn_perm(magic, pk[j], 0x04030402u));
+        lo = __builtin_amdgcn_fdot2(q01, a.p[2 * j], lo, false);
+        hi = __builtin_amdgcn_fdot2(q23, a.p[2 * j + 1], hi, false);
+    }
+    return fmaf(s, (lo + hi) - a.k1, z * a.sx);
+}
+
 // 16-bit layout: a lane's 128-bit load holds 8 consecutive weights, natural pairs.
 struct ActF16 {
     half2_t p[4];
@@ -147,8 +184,11 @@ __device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readf
 // ---------------------------------------------------------------- up-projection
 
 // Rows of all routed slots are laid end to end, weighted by their stored bytes (9 units per 4-bit row
-// pair, 32 per 16-bit one), and cut into equal shares, one per wavefront: every wavefront streams the
-// same number of bytes whatever the precision mix.
+// pair, 17 per 8-bit one, 32 per 16-bit one), and cut into equal shares, one per wavefront: every wavefront
+// streams the same number of bytes whatever the precision mix.
+__device__ __forceinline__ uint32_t row_units(int prec) {
+    return prec == MOE_PREC_INT4G64 ? 9u : (prec == MOE_PREC_INT8G64 ? 17u : 32u);
+}
 constexpr int kUpRowsI4 = 2;                    // rows per register buffer of the 4-bit path
 constexpr int kUpBufsI4 = 2;                    // register buffers in the ring of the 4-bit path
 constexpr uint32_t kMinUnitsPerWave = 100;      // cost units (9 per 4-bit row, 32 per 16-bit row) below which a share is too short
@@ -214,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     // the wavefront index goes through a scalar register: everything derived from it (row ranges, row base
     // addresses) is then uniform, and the loads below take the scalar-base + 32-bit lane-offset form
     uint32_t total = 0;
-    for (int s = 0; s < k; ++s) total += (uint32_t)f * (ex.e[expert_of(s)].prec == MOE_PREC_INT4G64 ? 9u : 32u);
+    for (int s = 0; s < k; ++s) total += (uint32_t)f * row_units(ex.e[expert_of(s)].prec);
     // A wavefront needs a dozen rows or so for its load pipeline to reach a steady state.  When the routed
     // experts are small (all 4-bit), half the workgroups take all the work and the others leave at once: the
     // launch shape is fixed on the host before the routing result exists, the work is only known here.
@@ -228,14 +268,14 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     uint32_t base = 0;
     for (int s = 0; s < k; ++s) {
         const DevExpert& ee = ex.e[expert_of(s)];
-        const bool int4 = ee.prec == MOE_PREC_INT4G64;
-        const uint32_t span = (uint32_t)f * (int4 ? 9u : 32u);
+        const bool int4 = ee.prec == MOE_PREC_INT4G64, int8 = ee.prec == MOE_PREC_INT8G64;
+        const uint32_t cost = row_units(ee.prec), span = (uint32_t)f * cost;
         // rows whose first cost unit falls in [lo, hi): ceil((lo - base) / cost) .. ceil((hi - base) / cost)
         const uint32_t l = lo > base ? (lo - base < span ? lo - base : span) : 0u;
         const uint32_t u = hi > base ? (hi - base < span ? hi - base : span) : 0u;
         // (the divisions run on the vector unit; move the uniform results back to scalar registers)
-        const int r0 = __builtin_amdgcn_readfirstlane((int)(int4 ? (l + 8u) / 9u : (l + 31u) / 32u));
-        const int r1 = __builtin_amdgcn_readfirstlane((int)(int4 ? (u + 8u) / 9u : (u + 31u) / 32u));
+        const int r0 = __builtin_amdgcn_readfirstlane((int)((l + cost - 1u) / cost));
+        const int r1 = __builtin_amdgcn_readfirstlane((int)((u + cost - 1u) / cost));
         base += span;
         // an expert that cannot run is left out here and reported by the down-projection launch
         if (r0 >= r1 || ee.resident != 1 || !ee.w1.data) continue;
@@ -344,6 +384,88 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+            }
+        } else if (int8) {
+            // 8-bit rows: one register buffer = one row of w1 and one of w3 (2 x d bytes), two buffers; scales and
+            // zeros travel as in the 4-bit path, as 1 KB runs of G rows through a wavefront-private LDS region.
+            constexpr int NL8 = d / 1024;                        // 128-bit loads per row
+            constexpr int gpr = d / 64;
+            constexpr int DPR = 16 * NCH;                        // dwords of scales per row
+            constexpr int G = ((256 / DPR) / 2) * 2;             // rows per run (8 at d = 4096), even
+            ActI8 act[NL8];
+            __shared__ __align__(16) uint8_t sz8_lds[4][4][1024];     // [wavefront][array][run]
+            uint8_t* const my_lds = &sz8_lds[wave_index()][0][0];
+            const gptr_t szm[4] = {scalar_ptr(ee.w1.scale), scalar_ptr(ee.w1.zero), scalar_ptr(ee.w3.scale),
+                                   scalar_ptr(ee.w3.zero)};
+            uint4_t sg[4];                                       // the run on its way to LDS
+            auto load_group = [&](int rg) {
+                int i = (4 * lane) / DPR;                        // the lane's four dwords belong to row rg + i
+                i = i < G ? i : G - 1;
+                const int row = (rg + i < r1) ? rg + i : r1 - 1; // rows past the end repeat the last one
+                const uint32_t off = (uint32_t)row * (gpr * 2) + (uint32_t)((4 * lane) % DPR) * 4;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) sg[a] = load_stream(at(szm[a], off));
+            };
+            auto publish_group = [&]() {
+                wave_lds_handover();   // the previous run has been read by every lane
+#pragma unroll
+                for (int a = 0; a < 4; ++a) *(uint4_t*)(my_lds + a * 1024 + lane * 16) = sg[a];
+                wave_lds_handover();
+            };
+            // scale or zero (array a) of row `in_group` of the current run for this lane's group of 64 columns in
+            // chunk c: half 16 c + lane / 4 of the row
+            const int lane_grp = (lane >> 2) * 2;
+            auto pick = [&](int a, int in_group, int c) {
+                return (float)*(const half_t*)(my_lds + a * 1024 + (in_group * DPR) * 4 + 32 * c + lane_grp);
+            };
+            struct Row8 {
+                uint4_t v1[NL8], v3[NL8];
+            };
+            const uint32_t lane_q = lane * 16;
+            auto load_row = [&](Row8& B, int r) {
+                const int row = r < r1 ? r : r1 - 1;             // a row past the end repeats the last one (never stored)
+                const gptr_t q1 = scalar_ptr(ee.w1.data + (size_t)row * d);      // uniform row bases
+                const gptr_t q3 = scalar_ptr(ee.w3.data + (size_t)row * d);
+#pragma unroll
+                for (int c = 0; c < NL8; ++c) {
+                    B.v1[c] = load_stream(at(q1, lane_q + c * 1024));
+                    B.v3[c] = load_stream(at(q3, lane_q + c * 1024));
+                }
+            };
+            auto compute_row = [&](const Row8& B, int r) {
+                const int in_group = (r - r0) % G;
+                float a = 0.0f, b = 0.0f;
+#pragma unroll
+                for (int c = 0; c < NL8; ++c) {
+                    a += dot_i8(B.v1[c], act[c], pick(0, in_group, c), pick(1, in_group, c));
+                    b += dot_i8(B.v3[c], act[c], pick(2, in_group, c), pick(3, in_group, c));
+                }
+                a = wave_total(a);
+                b = wave_total(b);
+                if (lane == 0 && r < r1) hs[r] = (half_t)silu_mul(a, b);
+            };
+            Row8 A, B;
+            load_row(A, r0);
+            load_group(r0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < NL8; ++c) load_act_i8(xin + c * 1024 + lane * 16, act[c]);
+            publish_group();
+            load_group(r0 + G);
+            __builtin_amdgcn_sched_barrier(0);
+            for (int r = r0; r < r1; r += 2) {
+                if (r > r0 && (r - r0) % G == 0) {               // a new run starts: it goes to LDS, the next is requested
+                    publish_group();
+                    load_group(r + G);
+                }
+                load_row(B, r + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                compute_row(A, r);
+                __builtin_amdgcn_sched_barrier(0);
+                if (r + 2 < r1) load_row(A, r + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                compute_row(B, r + 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
             constexpr int NL = d / 512;   // 128-bit loads per row
@@ -456,6 +578,54 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
                 for (int r = 0; r < kDownBatch; ++r)
                     acc[rb + kDownBatch + r] =
                         fmaf(g, dot_i4(B.pk[r], act, (float)B.sv[r], (float)B.zv[r]), acc[rb + kDownBatch + r]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if (ee.prec == MOE_PREC_INT8G64) {
+            // 8-bit rows: the wavefront's 2048 columns are two 128-bit loads per lane and row
+            ActI8 act[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) load_act_i8(hs + c * 1024 + lane * 16, act[c]);
+            const size_t gpr = f >> 6;
+            const uint8_t* q = ee.w2.data + (size_t)row0 * f + wave * 2048;           // uniform
+            const half_t* sc = ee.w2.scale + (size_t)row0 * gpr + wave * 32;
+            const half_t* zr = ee.w2.zero + (size_t)row0 * gpr + wave * 32;
+            const uint32_t lane_q = lane * 16, lane_g = (lane >> 2) * 2;
+            struct Batch {
+                uint4_t pk[kDownBatch][2];
+                half_t sv[kDownBatch][2], zv[kDownBatch][2];
+            };
+            auto load_batch = [&](Batch& B, int rb) {
+#pragma unroll
+                for (int r = 0; r < kDownBatch; ++r) {
+                    const gptr_t qr = scalar_ptr(q + (size_t)(rb + r) * f);
+                    const gptr_t sr = scalar_ptr(sc + (size_t)(rb + r) * gpr), zq = scalar_ptr(zr + (size_t)(rb + r) * gpr);
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        B.pk[r][c] = load_stream(at(qr, lane_q + c * 1024));
+                        B.sv[r][c] = load_half(at(sr, lane_g + c * 32));
+                        B.zv[r][c] = load_half(at(zq, lane_g + c * 32));
+                    }
+                }
+            };
+            auto use_batch = [&](const Batch& B, int rb) {
+#pragma unroll
+                for (int r = 0; r < kDownBatch; ++r) {
+                    const float p = dot_i8(B.pk[r][0], act[0], (float)B.sv[r][0], (float)B.zv[r][0]) +
+                                    dot_i8(B.pk[r][1], act[1], (float)B.sv[r][1], (float)B.zv[r][1]);
+                    acc[rb + r] = fmaf(g, p, acc[rb + r]);
+                }
+            };
+            Batch A, B;
+            load_batch(A, 0);
+#pragma unroll
+            for (int rb = 0; rb < kDownRows; rb += 2 * kDownBatch) {
+                load_batch(B, rb + kDownBatch);
+                __builtin_amdgcn_sched_barrier(0);
+                use_batch(A, rb);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rb + 2 * kDownBatch < kDownRows) load_batch(A, rb + 2 * kDownBatch);
+                __builtin_amdgcn_sched_barrier(0);
+                use_batch(B, rb + kDownBatch);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
