@@ -58,15 +58,8 @@ constexpr int kDecodeUpBlocks = 1024;
 
 // Which kernels serve T tokens of a block: T == 1 the batch-1 kernels, otherwise the matrix-core path when
 // the shape allows it, else the shape-agnostic kernels.
-// Calls on several tokens of a block that holds an 8-bit expert anywhere take the shape-agnostic kernels for every
-// expert (which expert a token meets is only known on the device); the one-token kernels take all three precisions.
-bool has_int8(const moe_layer* L) {
-    for (int e = 0; e < L->n_experts; ++e)
-        if (L->experts[e].prec == MOE_PREC_INT8G64) return true;
-    return false;
-}
 bool use_decode(const moe_layer* L, int T) { return T == 1 && decode_shape_ok(L->d_model, L->d_ff); }
-bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff) && !has_int8(L); }
+bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff); }
 
 MfmaPlan plan_for(const moe_layer* L, int rows) { return plan_mfma(rows, L->d_model, L->d_ff, L->n_experts); }
 

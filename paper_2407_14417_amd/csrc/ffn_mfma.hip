@@ -10,7 +10,8 @@
 // and turned into operand layout through a small wavefront-private LDS region; reading them directly in operand
 // layout would touch 16 half lines per instruction and leaves the memory pipeline, not the matrix cores, in charge.
 // 4-bit weights travel as codes and are expanded in registers (codes masked into the mantissa of an fp16
-// constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and zero).  Activations
+// constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and zero); 8-bit codes
+// likewise, with a byte permute in place of the masks.  Activations
 // are the B operand: a [16*CT, 128*SPB] tile per stage of the contraction, double-buffered in LDS and shared by
 // the 4 wavefronts.  Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one
 // activation row, so results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
@@ -89,6 +90,19 @@ __device__ __forceinline__ half8_t expand_word(uint32_t w, half2_t s2, half2_t z
     return half8_t{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
 }
 
+// Eight 8-bit codes (two words) -> their dequantized fp16 values, in column order.
+__device__ __forceinline__ half8_t expand_bytes(uint32_t w0, uint32_t w1, half2_t s2, half2_t z2, uint32_t m1024,
+                                                uint32_t m64x4) {
+    // a byte permute puts each code into the low byte of an fp16 whose high byte is 0x64: 1024 + code, exactly
+    const half2_t q01 = as_half2(__builtin_amdgcn_perm(m64x4, w0, 0x04010400u)) - as_half2(m1024);
+    const half2_t q23 = as_half2(__builtin_amdgcn_perm(m64x4, w0, 0x04030402u)) - as_half2(m1024);
+    const half2_t q45 = as_half2(__builtin_amdgcn_perm(m64x4, w1, 0x04010400u)) - as_half2(m1024);
+    const half2_t q67 = as_half2(__builtin_amdgcn_perm(m64x4, w1, 0x04030402u)) - as_half2(m1024);
+    const half2_t a = __builtin_elementwise_fma(q01, s2, z2), b = __builtin_elementwise_fma(q23, s2, z2);
+    const half2_t c = __builtin_elementwise_fma(q45, s2, z2), d = __builtin_elementwise_fma(q67, s2, z2);
+    return half8_t{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
 // What one workgroup works on, set up once by the kernel and handed to the precision-specific body.
 struct TileCtx {
     const half_t* in;        // activations
@@ -111,8 +125,9 @@ struct TileCtx {
 // NCT = 16-row activation tiles computed (exactly the tiles that hold rows), so the inner loops are
 // straight-line code.  SPB = 128-column steps per LDS stage (and per barrier): a launch with few activation
 // rows per chunk stages more columns at a time, so that the LDS buffers always hold 128 x 128 elements.
-template <bool UP, bool INT4, int NCT, int SPB, int NA>
+template <bool UP, int PREC, int NCT, int SPB, int NA>   // PREC: moe_prec of the expert
 __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
+    constexpr bool INT4 = PREC == MOE_PREC_INT4G64, INT8 = PREC == MOE_PREC_INT8G64, QUANT = INT4 || INT8;
     constexpr int NT = UP ? 32 * NA : 64 * NA;     // weight rows per workgroup: 16 NA / (matrices) per wavefront
     constexpr int kStride = SPB * kKTile * 2 + 16;     // bytes per activation row of an LDS stage (16 bytes of padding)
     constexpr int PPR = 16 * SPB;                      // 16-byte pieces per row of a stage
@@ -166,8 +181,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
         int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
         row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
-        wscale[t] = INT4 ? m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
-        wzero[t] = INT4 ? m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
+        wscale[t] = QUANT ? m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
+        wzero[t] = QUANT ? m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
     }
 
     float4_t acc[NA][NCT];
@@ -178,8 +193,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 
     // B operand of activation tile j, step q of the stage, sub-step s: lane (r16, c4) reads 8 elements of
     // activation row 16 j + r16
-    const int b_lane = r16 * kStride + (INT4 ? c4 * 64 : c4 * 16);
-    constexpr int b_sub = INT4 ? 16 : 64;
+    // (quantized weights: a lane owns 32 consecutive columns of the 128-column step, sub-step s its s-th eight of
+    // them -- a permutation of the contraction index that the activations follow)
+    const int b_lane = r16 * kStride + (QUANT ? c4 * 64 : c4 * 16);
+    constexpr int b_sub = QUANT ? 16 : 64;
 
     // Pipeline: at the first step of a stage the activation data of the next stage goes to the other LDS buffer
     // (its loads were issued a stage earlier) and the loads of the stage after that are issued; weights run three
@@ -189,7 +206,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     constexpr int G = SPB > 4 ? SPB : 4;
     uint32_t sz_cur[NA][2], sz_next[NA][2];
     const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
-    const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
+    const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(INT8 ? 0x64646464u : 0x54005400u);
     // scales and zeros of four steps with one load: lane (r16, c4) fetches the pair of groups of step 4 S + c4
     auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
         int step = 4 * S + c4;
@@ -206,9 +223,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     // back in operand layout.  A staging unit is UB bytes of every row: 4-bit, one line = 256 columns = two steps,
     // lane (r16, c4) takes slot 4 * (step & 1) + c4 as its 32 codes of a step; 16-bit, two lines = 128 columns = one
     // step, lane (r16, c4) takes slot 4 * sb + c4 as its 8 weights of sub-step sb.
-    constexpr int UL = INT4 ? 1 : 2;     // lines per row and unit
+    // 8-bit, one line = 128 columns = one step, lane (r16, c4) takes slots 2 c4 and 2 c4 + 1 as its 32 codes.
+    constexpr int UL = QUANT ? 1 : 2;    // lines per row and unit
     constexpr int UB = UL * 128;         // bytes per row and unit
-    constexpr int UA = INT4 ? 2 : 4;     // operand registers (128-bit) per A operand and unit
+    constexpr int UA = QUANT ? 2 : 4;    // operand registers (128-bit) per A operand and unit
     uint4_t stg[NA][2 * UL];             // staged loads of the next unit
     uint4_t apc[NA][UA];                 // the current unit in operand layout
     uint32_t goff[NA][2];                // per-lane byte offsets of the staged rows inside the weight matrix
@@ -221,12 +239,12 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     for (int t = 0; t < NA; ++t) {
         const int tile = UP ? (t >> 1) : t;
         const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
-        cbase[t] = scalar_ptr(m.data + (INT4 ? (c.k_begin >> 1) : c.k_begin * 2));
+        cbase[t] = scalar_ptr(m.data + (INT4 ? (c.k_begin >> 1) : INT8 ? c.k_begin : c.k_begin * 2));
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
             int row = c.n0 + wave * (NT / 4) + tile * 16 + 8 * hb + (lane >> 3);
             row = row < N ? row : N - 1;                           // rows past the end repeat the last row, never stored
-            goff[t][hb] = (uint32_t)row * (uint32_t)(INT4 ? (K >> 1) : 2 * K) + (lane & 7) * 16;
+            goff[t][hb] = (uint32_t)row * (uint32_t)(INT4 ? (K >> 1) : INT8 ? K : 2 * K) + (lane & 7) * 16;
         }
     }
     auto load_unit = [&](int unit) {           // a unit past the end repeats the last one (never used)
@@ -266,7 +284,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         for (int t = 0; t < NA; ++t)
 #pragma unroll
             for (int h = 0; h < UA; ++h) {
-                const int slot = (4 * h + c4 + shift) & (8 * UL - 1);
+                const int slot = INT8 ? 2 * c4 + h : (4 * h + c4 + shift) & (8 * UL - 1);
                 // the XOR touches the low three bits of the slot only: a piece stays inside its 128-byte line
                 apc[t][h] = *(const uint4_t*)(wreg + t * (16 * UB) + w_rd + ((slot ^ (r16 & 7)) * 16));
             }
@@ -276,7 +294,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     // stream, so the A operands skip LDS: lane (r16, c4) loads its 8 weights of every 32-column sub-step
     // straight from device memory (16 rows x 64 bytes per instruction), one step ahead, into the other half of a
     // two-step register ring.
-    constexpr bool DIRECT = !INT4 && NCT >= kDirectNCT;
+    constexpr bool DIRECT = !QUANT && NCT >= kDirectNCT;
     uint4_t ad[DIRECT ? 2 : 1][NA][4];
     uint32_t doff[NA];
 #pragma unroll
@@ -296,7 +314,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     };
 
     load_x(0);
-    if (INT4) load_sz(sz_cur, 0);
+    if (QUANT) load_sz(sz_cur, 0);
     if (DIRECT) {
         load_direct(0, 0);
     } else {
@@ -353,6 +371,40 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                         stage_to_lds();
                         load_unit((step >> 1) + 2);
                     }
+                } else if (INT8) {
+                    if (g % 4 == 0) {
+                        if (step > 0) {
+#pragma unroll
+                            for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+                        }
+                        load_sz(sz_next, step / 4 + 1);
+                    }
+                    lds_to_operands(step);
+                    half2_t s2[NA], z2[NA];
+                    const int src = (r16 + 16 * (g & 3)) * 4;       // the lane of this row that fetched this step's scales
+#pragma unroll
+                    for (int t = 0; t < NA; ++t) {
+                        const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][0]);
+                        const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][1]);
+                        s2[t] = as_half2(__builtin_amdgcn_perm(sd, sd, sel));
+                        z2[t] = as_half2(__builtin_amdgcn_perm(zd, zd, sel));
+                    }
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        half8_t af[NA];
+#pragma unroll
+                        for (int t = 0; t < NA; ++t)
+                            af[t] = expand_bytes(apc[t][sb >> 1][2 * (sb & 1)], apc[t][sb >> 1][2 * (sb & 1) + 1], s2[t], z2[t],
+                                                 m1024, m64);
+#pragma unroll
+                        for (int j2 = 0; j2 < NCT; ++j2) {
+                            const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
+#pragma unroll
+                            for (int t = 0; t < NA; ++t) acc[t][j2] = mfma16(af[t], b, acc[t][j2]);
+                        }
+                    }
+                    stage_to_lds();                                 // the step is used up: the next one takes its place
+                    load_unit(step + 2);
                 } else if (DIRECT) {
                     load_direct((g + 1) & 1, step + 1);
 #pragma unroll
@@ -415,7 +467,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     }
 }
 
-template <bool UP, int CT>
+// WIDE: the block holds 8-bit experts as well.  The 8-bit body needs more registers than the other two, and a
+// kernel's register count is that of its largest body, so blocks without 8-bit experts get a kernel without it
+// (and keep four wavefronts per SIMD at few rows per expert).  The wide kernel has bodies for 1, 2, 4 and 8 tiles.
+template <bool UP, int CT, bool WIDE>
 __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     constexpr int MC = 16 * CT;                  // activation rows per chunk
     constexpr int NA = CT <= 2 ? kNASmall : 4;   // A operands per wavefront
@@ -463,15 +518,22 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
         }
         return;
     }
-    const bool int4 = ee.prec == MOE_PREC_INT4G64;
+    const int prec = ee.prec;
     const int nct = (c.rows + 15) >> 4;          // 16-row tiles that hold any rows
     // the straight-line body for exactly the chunk's tiles where the launch can have that many (the clamp keeps
     // the smaller launches from instantiating bodies they never run)
 #define MOEMIX_BODY(n)                                                                                          \
     do {                                                                                                        \
-        if (int4) tile_body<UP, true, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                        \
-        else tile_body<UP, false, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                            \
+        if (prec == MOE_PREC_INT4G64) tile_body<UP, MOE_PREC_INT4G64, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base); \
+        else if (WIDE && prec == MOE_PREC_INT8G64) tile_body<UP, WIDE ? MOE_PREC_INT8G64 : MOE_PREC_FP16, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base); \
+        else tile_body<UP, MOE_PREC_FP16, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                    \
     } while (0)
+    if (WIDE) {
+        if (CT >= 8 && nct > 4) MOEMIX_BODY(8);
+        else if (CT >= 4 && nct > 2) MOEMIX_BODY(4);
+        else if (CT >= 2 && nct > 1) MOEMIX_BODY(2);
+        else MOEMIX_BODY(1);
+    } else
     if (CT >= 8 && nct > 7) MOEMIX_BODY(8);
     else if (CT >= 8 && nct > 6) MOEMIX_BODY(7);
     else if (CT >= 8 && nct > 5) MOEMIX_BODY(6);
@@ -483,7 +545,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
 #undef MOEMIX_BODY
 }
 
-template <bool UP, int CT>
+template <bool UP, int CT, bool WIDE>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     constexpr int NA = CT <= 2 ? kNASmall : 4;
     // activation stages + 4 wavefronts x NA operands of weight staging
@@ -496,28 +558,40 @@ void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     (void)hipGetDevice(&dev);
     const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;
     if (!(configured.load(std::memory_order_relaxed) & bit) || !bit) {
-        (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        (void)hipFuncSetAttribute((const void*)grouped_mfma_kernel<UP, CT, WIDE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)lds_max);
         configured.fetch_or(bit, std::memory_order_relaxed);
     }
-    grouped_mfma_kernel<UP, CT><<<grid, 256, lds_bytes, st>>>(a);
+    grouped_mfma_kernel<UP, CT, WIDE><<<grid, 256, lds_bytes, st>>>(a);
+}
+
+template <bool UP, bool WIDE>
+void launch_ct_w(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
+    switch (ct) {
+        case 1: launch_one<UP, 1, WIDE>(a, grid, st); break;
+        case 2: launch_one<UP, 2, WIDE>(a, grid, st); break;
+        case 4: launch_one<UP, 4, WIDE>(a, grid, st); break;
+        default: launch_one<UP, 8, WIDE>(a, grid, st); break;
+    }
+}
+
+bool any_int8(const DevExperts& ex, int E) {
+    for (int e = 0; e < E; ++e)
+        if (ex.e[e].prec == MOE_PREC_INT8G64) return true;
+    return false;
 }
 
 template <bool UP>
 void launch_ct(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
-    switch (ct) {
-        case 1: launch_one<UP, 1>(a, grid, st); break;
-        case 2: launch_one<UP, 2>(a, grid, st); break;
-        case 4: launch_one<UP, 4>(a, grid, st); break;
-        default: launch_one<UP, 8>(a, grid, st); break;
-    }
+    if (any_int8(a.ex, a.E)) launch_ct_w<UP, true>(a, ct, grid, st);
+    else launch_ct_w<UP, false>(a, ct, grid, st);
 }
 
 // Weight staging needs 4 KB of LDS per A operand for 16-bit experts, 2 KB for 4-bit ones.
 int staging_unit_bytes(const DevExperts& ex, int E, const RowMap& rows) {
-    if (rows.direct_expert >= 0) return ex.e[rows.direct_expert].prec == MOE_PREC_INT4G64 ? 2048 : 4096;
+    if (rows.direct_expert >= 0) return ex.e[rows.direct_expert].prec == MOE_PREC_FP16 ? 4096 : 2048;
     for (int e = 0; e < E; ++e)
-        if (ex.e[e].resident == 1 && ex.e[e].prec != MOE_PREC_INT4G64) return 4096;
+        if (ex.e[e].resident == 1 && ex.e[e].prec == MOE_PREC_FP16) return 4096;
     return 2048;
 }
 
