@@ -15,8 +15,8 @@ of the dominant kernel (the up-projection: 2/3 of the weights) in an eager pass 
 
 Besides the headline the same JSON line carries, under `configs`, the other workloads of the same layer shape,
 each timed the same way and each with the parity metrics of one of its steps against the CPU oracle:
-`decode_int4_only` / `decode_fp16_only` (batch-1 decode with every expert 4-bit / 16-bit: the all-4-bit pair is
-the case the >= 70 % of HBM peak target is stated for), `batched` (16 tokens per step, all experts 4-bit,
+`decode_int4_only` / `decode_fp16_only` / `decode_int8_only` (batch-1 decode with every expert 4-bit / 16-bit / 8-bit:
+the all-4-bit pair is the case the >= 70 % of HBM peak target is stated for), `batched` (16 tokens per step, all experts 4-bit,
 uniform-random gate matrix), `prefill` (512 tokens per step, experts 0-1 16-bit and 2-7 4-bit, Zipf(1.2) logit
 offsets), `chain` (32 x (RMSNorm -> block -> residual), 1 token, a seeded random half of the 256 experts 4-bit; a
 step is one pass through all 32 blocks).  `stream_ceiling` is a plain streaming-read kernel at the byte counts of
@@ -50,6 +50,10 @@ WORKLOADS = {
                              name="batch-1 decode, same layer shape, every expert uint4 g64 (the all-4-bit routed pair)"),
     "decode_fp16_only": dict(T=1, int4=(), router="normal", zipf=None, pool=4, steps=40, warmup=8, bound="hbm",
                              name="batch-1 decode, same layer shape, every expert fp16"),
+    "decode_int8_only": dict(T=1, int4=(), int8=tuple(range(8)), router="normal", zipf=None, pool=6, steps=40, warmup=8,
+                             bound="hbm",
+                             name="batch-1 decode, same layer shape, every expert uint8 g64 (the precision of the "
+                                  "paper's homogeneous 8-bit model)"),
     "batched": dict(T=16, int4=tuple(range(8)), router="uniform", zipf=None, pool=4, steps=20, warmup=4,
                     bound="hbm",
                     name="Mixtral-shaped layer, fully quantized batched decode: 8 experts all uint4 g64, top-2, "
@@ -66,7 +70,7 @@ WORKLOADS = {
                   name="32-layer chained MoE decode step: 32 x (RMSNorm 1e-5 -> 8-expert top-2 block -> residual), "
                        "1 token, 128 of 256 experts uint4 g64 by seeded random mask"),
 }
-EXTRA_CONFIGS = ("decode_int4_only", "decode_fp16_only", "batched", "prefill", "chain")
+EXTRA_CONFIGS = ("decode_int4_only", "decode_fp16_only", "decode_int8_only", "batched", "prefill", "chain")
 
 
 def traffic_ratio(profile_name: str, key: str):
@@ -147,6 +151,8 @@ def host_layer(wl, seed, layer, need):
               for i, s in enumerate(((F, D), (F, D), (D, F)))]
         if e in wl["int4"]:
             experts.append(orc.Expert(*[orc.quantize_int4(w) for w in ws]))
+        elif e in wl.get("int8", ()):
+            experts.append(orc.Expert(*[orc.quantize_int8(w) for w in ws]))
         else:
             experts.append(orc.Expert(*[orc.Mat(w) for w in ws]))
     return wg, bias, experts
@@ -202,7 +208,7 @@ def run_layer_workload(args, wl, mm, workload, torch, np, headline: bool):
     steps = (args.steps or wl["steps"]) if headline else wl["steps"]
     warmup = (args.warmup if args.warmup is not None else wl["warmup"]) if headline else wl["warmup"]
     layers = [workload.device_layer(D, F, E, K, wl["int4"], seed=args.seed, layer=l, router=wl["router"],
-                                    zipf=wl["zipf"]) for l in range(pool)]
+                                    zipf=wl["zipf"], int8_experts=wl.get("int8", ())) for l in range(pool)]
     n_tok = steps + warmup
     x_all = workload.device_tokens(n_tok * T, D, seed=args.seed).reshape(n_tok, T, D)
     out_all = torch.empty((n_tok, T, D), dtype=torch.float16, device="cuda")
@@ -242,8 +248,9 @@ def run_layer_workload(args, wl, mm, workload, torch, np, headline: bool):
                     "frac_of_hbm_peak_on_bytes": GBps / HBM_PEAK_GBPS})
     if T == 1:
         n_int4 = np.array([sum(int(e) in wl["int4"] for e in idx[j, 0]) for j in range(steps)])
-        res["routed_pairs"] = {name: int((n_int4 == kind).sum())
-                               for kind, name in ((0, "fp16+fp16"), (1, "fp16+int4"), (2, "int4+int4"))}
+        if not wl.get("int8"):
+            res["routed_pairs"] = {name: int((n_int4 == kind).sum())
+                                   for kind, name in ((0, "fp16+fp16"), (1, "fp16+int4"), (2, "int4+int4"))}
     else:
         counts = np.stack([np.bincount(idx[j].reshape(-1), minlength=E) for j in range(steps)])
         res["rows_per_expert_mean"] = [float(c) for c in counts.mean(axis=0)]
@@ -302,7 +309,7 @@ def run_layer_workload(args, wl, mm, workload, torch, np, headline: bool):
             roof["traffic_source"] = f"profiles/{prof} (rocprofv3 --pmc FETCH_SIZE, copy-calibrated): " \
                                      f"fetched/algorithmic = {ratio}"
         roof["algorithmic_bytes_per_launch"] = float(up_bytes.mean())
-        if T == 1:
+        if T == 1 and not wl.get("int8"):
             by_pair = {}
             for kind, name in ((0, "fp16+fp16"), (1, "fp16+int4"), (2, "int4+int4")):
                 sel = n_int4 == kind
@@ -593,8 +600,8 @@ def main() -> int:
         result["stream_ceiling"] = stream_ceiling(mm, torch)
     cpu_tokens = args.cpu_tokens
     if cpu_tokens < 0:
-        cpu_tokens = {"decode": 48, "decode_int4_only": 48, "decode_fp16_only": 24, "batched": 48, "prefill": 64,
-                      "chain": 0, "offload": 0}[args.workload]
+        cpu_tokens = {"decode": 48, "decode_int4_only": 48, "decode_fp16_only": 24, "decode_int8_only": 32, "batched": 48,
+                      "prefill": 64, "chain": 0, "offload": 0}[args.workload]
     if cpu_tokens > 0 and "int4" in wl:
         result["cpu_baseline"] = cpu_baseline(wl, args.seed, cpu_tokens)
     result["bench_wall_s"] = round(time.perf_counter() - t_start, 1)

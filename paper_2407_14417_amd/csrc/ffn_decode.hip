@@ -198,7 +198,9 @@ constexpr uint32_t kMinUnitsPerWave = 100;      // cost units (9 per 4-bit row, 
 // device memory sits idle; here every workgroup evaluates the gating network for the one token by itself, from
 // the 64 KB gate matrix that all of them read out of L2, and goes straight on to its share of the weights.
 // Workgroup 0 also writes the routing result for the down-projection launch and for the caller.
-template <int NCH, bool ROUTE>   // NCH = d_model / 2048
+// WIDE: the block holds 8-bit experts as well; blocks without them get a kernel without that branch (the code the
+// compiler makes for the other two precisions is then exactly what it is without the third).
+template <int NCH, bool ROUTE, bool WIDE>   // NCH = d_model / 2048
 __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const int32_t* __restrict__ idx,
                                                          const half_t* __restrict__ x, int f, int k,
                                                          half_t* __restrict__ h, int32_t* status, const GateArgs ga) {
@@ -254,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     // the wavefront index goes through a scalar register: everything derived from it (row ranges, row base
     // addresses) is then uniform, and the loads below take the scalar-base + 32-bit lane-offset form
     uint32_t total = 0;
-    for (int s = 0; s < k; ++s) total += (uint32_t)f * row_units(ex.e[expert_of(s)].prec);
+    for (int s = 0; s < k; ++s) total += (uint32_t)f * (WIDE ? row_units(ex.e[expert_of(s)].prec) : (ex.e[expert_of(s)].prec == MOE_PREC_INT4G64 ? 9u : 32u));
     // A wavefront needs a dozen rows or so for its load pipeline to reach a steady state.  When the routed
     // experts are small (all 4-bit), half the workgroups take all the work and the others leave at once: the
     // launch shape is fixed on the host before the routing result exists, the work is only known here.
@@ -268,14 +270,16 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
     uint32_t base = 0;
     for (int s = 0; s < k; ++s) {
         const DevExpert& ee = ex.e[expert_of(s)];
-        const bool int4 = ee.prec == MOE_PREC_INT4G64, int8 = ee.prec == MOE_PREC_INT8G64;
-        const uint32_t cost = row_units(ee.prec), span = (uint32_t)f * cost;
+        const bool int4 = ee.prec == MOE_PREC_INT4G64, int8 = WIDE && ee.prec == MOE_PREC_INT8G64;
+        const uint32_t cost = WIDE ? row_units(ee.prec) : (int4 ? 9u : 32u), span = (uint32_t)f * cost;
         // rows whose first cost unit falls in [lo, hi): ceil((lo - base) / cost) .. ceil((hi - base) / cost)
         const uint32_t l = lo > base ? (lo - base < span ? lo - base : span) : 0u;
         const uint32_t u = hi > base ? (hi - base < span ? hi - base : span) : 0u;
         // (the divisions run on the vector unit; move the uniform results back to scalar registers)
-        const int r0 = __builtin_amdgcn_readfirstlane((int)((l + cost - 1u) / cost));
-        const int r1 = __builtin_amdgcn_readfirstlane((int)((u + cost - 1u) / cost));
+        const int r0 = __builtin_amdgcn_readfirstlane(
+            (int)(WIDE ? (l + cost - 1u) / cost : (int4 ? (l + 8u) / 9u : (l + 31u) / 32u)));
+        const int r1 = __builtin_amdgcn_readfirstlane(
+            (int)(WIDE ? (u + cost - 1u) / cost : (int4 ? (u + 8u) / 9u : (u + 31u) / 32u)));
         base += span;
         // an expert that cannot run is left out here and reported by the down-projection launch
         if (r0 >= r1 || ee.resident != 1 || !ee.w1.data) continue;
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
                     }
                 }
             }
-        } else if (int8) {
+        } else if (WIDE && int8) {
             // 8-bit rows: one register buffer = one row of w1 and one of w3 (2 x d bytes), two buffers; scales and
             // zeros travel as in the 4-bit path, as 1 KB runs of G rows through a wavefront-private LDS region.
             constexpr int NL8 = d / 1024;                        // 128-bit loads per row
@@ -520,6 +524,7 @@ __global__ __launch_bounds__(256, 2) void decode_up_kernel(DevExperts ex, const 
 constexpr int kDownRows = 16;
 constexpr int kDownBatch = 4;
 
+template <bool WIDE>   // WIDE: with the branch for 8-bit experts
 __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const int32_t* __restrict__ idx,
                                                            const float* __restrict__ gate,
                                                            const half_t* __restrict__ h, int d, int f, int k,
@@ -580,7 +585,7 @@ __global__ __launch_bounds__(512) void decode_down_kernel(DevExperts ex, const i
                         fmaf(g, dot_i4(B.pk[r], act, (float)B.sv[r], (float)B.zv[r]), acc[rb + kDownBatch + r]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        } else if (ee.prec == MOE_PREC_INT8G64) {
+        } else if (WIDE && ee.prec == MOE_PREC_INT8G64) {
             // 8-bit rows: the wavefront's 2048 columns are two 128-bit loads per lane and row
             ActI8 act[2];
 #pragma unroll
@@ -699,28 +704,43 @@ __global__ void single_route_kernel(int32_t* idx, float* gate, int expert) {
 
 bool decode_shape_ok(int d, int f) { return d % 2048 == 0 && d <= 8192 && f % 2048 == 0 && f <= 16384 && d % kDownRows == 0; }
 
-template <bool ROUTE>
+static bool any_int8(const DevExperts& ex) {
+    for (int e = 0; e < MOE_MAX_EXPERTS; ++e)
+        if (ex.e[e].prec == MOE_PREC_INT8G64 && ex.e[e].w1.data) return true;
+    return false;
+}
+
+template <bool ROUTE, bool WIDE>
 static void launch_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
                       int32_t* status, int blocks, const GateArgs& ga, hipStream_t st) {
     switch (d / 2048) {
-        case 1: decode_up_kernel<1, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
-        case 2: decode_up_kernel<2, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
-        case 3: decode_up_kernel<3, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
-        default: decode_up_kernel<4, ROUTE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        case 1: decode_up_kernel<1, ROUTE, WIDE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        case 2: decode_up_kernel<2, ROUTE, WIDE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        case 3: decode_up_kernel<3, ROUTE, WIDE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
+        default: decode_up_kernel<4, ROUTE, WIDE><<<blocks, 256, 0, st>>>(ex, idx, x, f, k, h, status, ga); break;
     }
 }
 
 void launch_decode_up(const DevExperts& ex, const int32_t* idx, const half_t* x, int d, int f, int k, half_t* h,
                       int32_t* status, int blocks, hipStream_t st, const GateArgs* gating) {
     TraceScope trace(kKernelUp, st);
-    if (gating) launch_up<true>(ex, idx, x, d, f, k, h, status, blocks, *gating, st);
-    else launch_up<false>(ex, idx, x, d, f, k, h, status, blocks, GateArgs{}, st);
+    const bool wide = any_int8(ex);
+    if (gating) {
+        if (wide) launch_up<true, true>(ex, idx, x, d, f, k, h, status, blocks, *gating, st);
+        else launch_up<true, false>(ex, idx, x, d, f, k, h, status, blocks, *gating, st);
+    } else {
+        if (wide) launch_up<false, true>(ex, idx, x, d, f, k, h, status, blocks, GateArgs{}, st);
+        else launch_up<false, false>(ex, idx, x, d, f, k, h, status, blocks, GateArgs{}, st);
+    }
 }
 
 void launch_decode_down(const DevExperts& ex, const int32_t* idx, const float* gate, const half_t* h, int d, int f,
                         int k, const half_t* residual, half_t* out, int32_t* status, hipStream_t st, float* out32) {
     TraceScope trace(kKernelDown, st);
-    decode_down_kernel<<<d / kDownRows, (f / 2048) * 64, 0, st>>>(ex, idx, gate, h, d, f, k, residual, out, out32, status);
+    if (any_int8(ex))
+        decode_down_kernel<true><<<d / kDownRows, (f / 2048) * 64, 0, st>>>(ex, idx, gate, h, d, f, k, residual, out, out32, status);
+    else
+        decode_down_kernel<false><<<d / kDownRows, (f / 2048) * 64, 0, st>>>(ex, idx, gate, h, d, f, k, residual, out, out32, status);
 }
 
 void launch_single_route(int32_t* idx, float* gate, int expert, hipStream_t st) {
