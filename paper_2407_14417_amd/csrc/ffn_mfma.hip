@@ -27,11 +27,16 @@ namespace {
 // Weights of launches with few activation rows per expert are read once, in whole lines: streamed past the caches'
 // replacement order.
 constexpr int kTemporalNA = 4;     // A operands per wavefront from which on weight lines are kept for sibling chunks
-constexpr int kDirectNCT = 8;      // activation tiles per chunk from which on 16-bit weights go straight to registers
+constexpr int kDirectNCT = 5;      // activation tiles per chunk from which on 16-bit weights go straight to registers
+                                   // (launches with 128-row chunks only)
 constexpr int kNASmall = 2;        // A operands per wavefront of launches with at most 32 rows per chunk
 constexpr int kSPBMax = 2;         // most 128-column steps per LDS stage
 constexpr int spb_for(int ct) { return (8 / ct) < kSPBMax ? (8 / ct) : kSPBMax; }
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
+constexpr int kDirectRows = 256;            // most activation rows of a chunk of a 16-bit expert (direct_body)
+#ifndef MOEMIX_SB
+#define MOEMIX_SB __builtin_amdgcn_sched_barrier(0)
+#endif
 
 struct MfmaArgs {
     DevExperts ex;
@@ -61,6 +66,16 @@ __device__ __forceinline__ gptr_t scalar_ptr(const void* p) {
 __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
+
+// The same product with the accumulator tied to one register tuple by construction: in long straight-line loops the
+// compiler otherwise unties some products (writes the sum to a new tuple), leaves every accumulator somewhere else
+// at the end of an iteration and copies them all back at its head.  The instruction is opaque to the compiler's
+// hazard handling: a reader of the accumulators that is not such a product has to follow mfma_settle().
+__device__ __forceinline__ void mfma16_tied(float4_t& c, half8_t a, half8_t b) {
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+// More wait states than the longest interval the hardware wants between a matrix product and a read of its result.
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
 // (a & mask) | bits in one instruction: the mask travels in a scalar register, the OR-ed bits in a vector one
 // (the instruction may read a single scalar operand, which is why the compiler does not form it by itself).
@@ -112,10 +127,47 @@ struct TileCtx {
     int begin, m0, rows;     // grouped rows [begin + m0, begin + m0 + rows)
     int n0;                  // first weight row of the workgroup
     int k_begin, n_steps;    // contraction range [k_begin, k_begin + 128 n_steps)
+    int rot;                 // the workgroup walks the range from step rot on, wrapping around (a multiple of 4; see below)
     int mc;                  // rows per LDS buffer (16 * ct of the launch)
     int unit_bytes;          // LDS bytes per A operand of the weight staging regions (2048: 4-bit only, 4096)
     uint8_t* lds;
 };
+
+// Results of one workgroup: lane (r16, c4) holds, for activation row 16 j + r16, weight rows
+// 16 tile + 4 c4 + (0..3) of the wavefront's NT/4 rows.
+template <bool UP, int NCT, int NA>
+__device__ __forceinline__ void store_results(const TileCtx& c, const float4_t (&acc)[NA][NCT], void* out_base, int wave,
+                                              int r16, int c4) {
+    constexpr int NT = UP ? 32 * NA : 64 * NA;
+    const int N = c.N;
+#pragma unroll
+    for (int j = 0; j < NCT; ++j) {
+        const int rr = 16 * j + r16;
+        if (rr < c.rows) {
+            const size_t g = (size_t)(c.begin + c.m0 + rr);
+            if (UP) {
+                half_t* h = (half_t*)out_base + g * N;
+#pragma unroll
+                for (int tile = 0; tile < NA / 2; ++tile) {
+                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
+                    if (col < N) {
+                        half4_t o;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[v] = (half_t)silu_mul(acc[2 * tile][j][v], acc[2 * tile + 1][j][v]);
+                        *(half4_t*)(h + col) = o;
+                    }
+                }
+            } else {
+                float* y = (float*)out_base + g * N;
+#pragma unroll
+                for (int tile = 0; tile < NA; ++tile) {
+                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
+                    if (col < N) *(float4_t*)(y + col) = acc[tile][j];
+                }
+            }
+        }
+    }
+}
 
 // A wavefront holds NA A operands (16-row tiles of weights) per step.  UP: two matrices (w1, w3), NA/2 tiles each
 // (workgroup of 4 wavefronts: 32 NA rows); down: one matrix (w2), NA tiles (workgroup: 64 NA rows).  NA = 4 for
@@ -155,6 +207,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     auto load_x = [&](int stage) {
         int step = stage * SPB + pstep;
         step = step < last ? step : last;
+        step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
 #pragma unroll
         for (int i = 0; i < NP; ++i) xr[i] = *(const uint4_t*)(xrow[i] + step * kKTile);
     };
@@ -211,6 +264,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
         int step = 4 * S + c4;
         step = step < last ? step : last;
+        step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
 #pragma unroll
         for (int t = 0; t < NA; ++t) {
             dst[t][0] = *(const uint32_t*)(wscale[t] + step * 2);
@@ -249,6 +303,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     }
     auto load_unit = [&](int unit) {           // a unit past the end repeats the last one (never used)
         unit = unit < last_unit ? unit : last_unit;
+        {   // (a rotated range has an even number of steps: whole units)
+            const int urot = INT4 ? c.rot >> 1 : c.rot, units = INT4 ? n_steps >> 1 : n_steps;
+            if (c.rot) unit = unit + urot < units ? unit + urot : unit + urot - units;
+        }
         // 4-bit, odd number of steps: the last pair's second half would leave the row only in the last row of the
         // last split, so the pair is moved back by one step there (its second half is then never used)
         const int byte0 = (!INT4 || 2 * unit + 2 <= n_steps) ? unit * UB : unit * UB - 64;
@@ -290,38 +348,11 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             }
     };
 
-    // 16-bit weights of a full chunk (8 activation tiles): the product is bound by LDS traffic, not by the weight
-    // stream, so the A operands skip LDS: lane (r16, c4) loads its 8 weights of every 32-column sub-step
-    // straight from device memory (16 rows x 64 bytes per instruction), one step ahead, into the other half of a
-    // two-step register ring.
-    constexpr bool DIRECT = !QUANT && NCT >= kDirectNCT;
-    uint4_t ad[DIRECT ? 2 : 1][NA][4];
-    uint32_t doff[NA];
-#pragma unroll
-    for (int t = 0; t < NA; ++t) {
-        const int tile = UP ? (t >> 1) : t;
-        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
-        row = row < N ? row : N - 1;
-        doff[t] = (uint32_t)row * (uint32_t)(2 * K) + c4 * 16;
-    }
-    auto load_direct = [&](int half, int step) {
-        step = step < last ? step : last;
-#pragma unroll
-        for (int t = 0; t < NA; ++t)
-#pragma unroll
-            for (int sb = 0; sb < 4; ++sb)
-                ad[half][t][sb] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + step * 256 + sb * 64);
-    };
-
     load_x(0);
     if (QUANT) load_sz(sz_cur, 0);
-    if (DIRECT) {
-        load_direct(0, 0);
-    } else {
-        load_unit(0);
-        stage_to_lds();
-        load_unit(1);
-    }
+    load_unit(0);
+    stage_to_lds();
+    load_unit(1);
     store_x(0);
     load_x(1);
     __syncthreads();
@@ -405,18 +436,6 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     }
                     stage_to_lds();                                 // the step is used up: the next one takes its place
                     load_unit(step + 2);
-                } else if (DIRECT) {
-                    load_direct((g + 1) & 1, step + 1);
-#pragma unroll
-                    for (int sb = 0; sb < 4; ++sb) {
-#pragma unroll
-                        for (int j2 = 0; j2 < NCT; ++j2) {
-                            const half8_t b = *(const half8_t*)(xb + j2 * 16 * kStride + sb * b_sub);
-#pragma unroll
-                            for (int t = 0; t < NA; ++t)
-                                acc[t][j2] = mfma16(__builtin_bit_cast(half8_t, ad[DIRECT ? (g & 1) : 0][t][sb]), b, acc[t][j2]);
-                        }
-                    }
                 } else {
                     lds_to_operands(step);
 #pragma unroll
@@ -437,34 +456,197 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         }
     }
 
-    // ---- results: lane (r16, c4) holds, for activation row 16 j + r16, weight rows 16 tile + 4 c4 + (0..3)
+    store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
+}
+
+// 16-bit weights against chunks of many activation rows.  A compute unit cannot draw more than about 25 GB/s of
+// weights out of device memory (measured with a bare read kernel of the same access pattern), and a 16-bit weight
+// brings only 2 products per activation row, so such a workgroup is bound by its weight stream unless it has some
+// hundred rows to multiply: chunks of 16-bit experts therefore hold up to 256 rows (NCT <= 16 tiles, all 256
+// accumulation registers), which halves the number of times an expert's weights are read.
+// A operands skip LDS: lane (r16, c4) loads its 8 weights of every 32-column sub-step straight from device memory
+// (16 rows x 64 bytes per instruction) into a ring of R sub-step slots, R sub-steps ahead of their use.
+// Activations are staged through registers into an LDS stage of [rows][128 columns] without padding: piece p
+// (16 bytes) of row r sits in slot p ^ (r & 15) of the row, so that the 16 lanes of a B operand read (rows r .. r + 15
+// at one piece index) hit 16 different slots, as do the 16 lanes that write one row.
+// B operands are read from LDS one unit (at most 8 tiles of one sub-step) ahead into a second register set, also
+// across the end of a step: the workgroup's one barrier per step sits before the last unit, whose reads were issued
+// before it; after it the stage just read out is free for the stage after the next one, and the other stage
+// (written before the barrier) is read for the next step's first unit.
+// The order of loads, LDS reads and products is pinned group by group (one B operand read per NA products); left
+// to itself the compiler issues the weight loads at the end of the step that precedes their use and waits for
+// every B operand it has just asked for.
+template <bool UP, int NCT>
+__device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
+    constexpr int NA = 4;
+    constexpr int NT = UP ? 32 * NA : 64 * NA;
+    constexpr int R = NCT > 8 ? 4 : 8;                 // ring slots = sub-steps of weights in flight
+    constexpr int U = NCT > 8 ? 2 : 1;                 // units (B register sets' worth of tiles) per sub-step
+    constexpr int NU0 = NCT > 8 ? 8 : NCT;             // tiles in a sub-step's first unit; the second holds the rest
+    constexpr int kRowBytes = kKTile * 2;              // one activation row of a stage: 256 bytes, 16 slots
+    constexpr int kStageBytes = kDirectRows * kRowBytes;
+    const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, c4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = c.K, N = c.N, n_steps = c.n_steps;
+    const int last = n_steps - 1, last_sub = 4 * n_steps - 1;
+
+    // ---- activation pieces this thread stages: 16-byte piece tid & 15 of rows (tid >> 4) + 16 i, into slot
+    // (tid & 15) ^ (tid >> 4) of the row.  Rows past the end of the chunk repeat its last row (their products are
+    // computed and never stored).  At most 8 pieces are in registers at a time: chunks of more than 8 tiles stage
+    // a stage in two batches.
+    constexpr int XB = NCT > 8 ? 8 : NCT;              // pieces per batch
+    const gptr_t xbase = scalar_ptr(c.in + c.k_begin);
+    uint32_t xoff[NCT];                                // byte offsets: the activations of one call stay below 4 GB
 #pragma unroll
-    for (int j = 0; j < NCT; ++j) {
-        const int rr = 16 * j + r16;
-        if (rr < c.rows) {
-            const size_t g = (size_t)(c.begin + c.m0 + rr);
-            if (UP) {
-                half_t* h = (half_t*)out_base + g * N;
+    for (int i = 0; i < NCT; ++i) {
+        int rr = (tid >> 4) + 16 * i;
+        rr = rr < c.rows ? rr : c.rows - 1;
+        const int g = c.begin + c.m0 + rr;
+        const uint32_t src = (UP && c.perm) ? (uint32_t)(c.perm[g] / c.top_k) : (uint32_t)g;
+        xoff[i] = src * (uint32_t)K * 2 + (tid & 15) * 16;
+    }
+    uint4_t xr[XB];
+    uint8_t* const xst = c.lds + (tid >> 4) * kRowBytes + (((tid & 15) ^ (tid >> 4)) * 16);
+    auto load_x1 = [&](int i, int stage) {             // piece i of the thread, stage `stage` of the contraction
+        int phys = stage < last ? stage : last;
+        phys = phys + c.rot < n_steps ? phys + c.rot : phys + c.rot - n_steps;
+        xr[i % XB] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + xoff[i] + phys * kRowBytes);
+    };
+    auto store_x1 = [&](int i, int stage) {            // ... into LDS buffer stage & 1
+        *(uint4_t*)(xst + (stage & 1) * kStageBytes + i * (16 * kRowBytes)) = xr[i % XB];
+    };
+
+    // ---- weights: row r16 of each of the wavefront's NA tiles, 16 bytes at c4 * 16 of every 64-byte sub-step
+    gptr_t cbase[NA];
+    uint32_t doff[NA];
 #pragma unroll
-                for (int tile = 0; tile < NA / 2; ++tile) {
-                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
-                    if (col < N) {
-                        half4_t o;
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
+        const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+        cbase[t] = scalar_ptr(m.data + c.k_begin * 2);
+        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
+        row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
+        doff[t] = (uint32_t)row * (uint32_t)(2 * K) + c4 * 16;
+    }
+    uint4_t ar[R][NA];
+    auto load_a = [&](int slot, int sub) {                         // sub-steps past the end repeat the last one
+        sub = sub < last_sub ? sub : last_sub;
+        sub = sub + 4 * c.rot <= last_sub ? sub + 4 * c.rot : sub + 4 * c.rot - 4 * n_steps;
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) o[v] = (half_t)silu_mul(acc[2 * tile][j][v], acc[2 * tile + 1][j][v]);
-                        *(half4_t*)(h + col) = o;
+        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + sub * 64);
+    };
+
+    float4_t acc[NA][NCT];
+#pragma unroll
+    for (int t = 0; t < NA; ++t)
+#pragma unroll
+        for (int j = 0; j < NCT; ++j) acc[t][j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // B operand of tile j, sub-step sb: row 16 j + r16, piece 4 sb + c4, which sits in slot (4 sb + c4) ^ r16
+    int b_off[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) b_off[sb] = r16 * kRowBytes + (((4 * sb + c4) ^ r16) * 16);
+    half8_t bq[2][8];
+    auto read_unit = [&](half8_t (&dst)[8], const uint8_t* stage_base, int sb, int h) {
+#pragma unroll
+        for (int j = 0; j < (h ? NCT - NU0 : NU0); ++j)
+            dst[j] = *(const half8_t*)(stage_base + b_off[sb] + (8 * h + j) * (16 * kRowBytes));
+    };
+
+    // Stage 0 (and, for chunks of more than 8 tiles, the second batch of it) goes to LDS here; the batch that is in
+    // registers when the loop starts is what the loop's schedule expects there: all of stage 1 (one batch per stage),
+    // or the second batch of stage 1 (two).  The ring's loads go out last.
+    if (U == 1) {
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) load_x1(i, 0);
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) { store_x1(i, 0); load_x1(i, 1); }
+    } else {
+#pragma unroll
+        for (int i = 0; i < XB; ++i) load_x1(i, 0);
+#pragma unroll
+        for (int i = 0; i < XB; ++i) { store_x1(i, 0); if (XB + i < NCT) load_x1(XB + i, 0); }
+#pragma unroll
+        for (int i = 0; i < XB; ++i) { if (XB + i < NCT) store_x1(XB + i, 0); load_x1(i, 1); }
+#pragma unroll
+        for (int i = 0; i < XB; ++i) { store_x1(i, 1); if (XB + i < NCT) load_x1(XB + i, 1); }
+    }
+    MOEMIX_SB;
+#pragma unroll
+    for (int u = 0; u < R; ++u) load_a(u, u);
+    MOEMIX_SB;
+    __syncthreads();
+    read_unit(bq[0], c.lds, 0, 0);
+    MOEMIX_SB;
+
+    for (int base = 0; base < n_steps; base += R / 4) {            // (the number of steps is even here)
+#pragma unroll
+        for (int g = 0; g < R / 4; ++g) {
+            const int step = base + g;
+            const uint8_t* const cur = c.lds + (step & 1) * kStageBytes;
+            const uint8_t* const nxt = c.lds + ((step + 1) & 1) * kStageBytes;
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                const int slot = (4 * g + sb) % R;
+#pragma unroll
+                for (int h = 0; h < U; ++h) {
+                    const int v = sb * U + h;                      // unit of the step; B register set v & 1
+                    const bool last_unit = v == 4 * U - 1;
+                    // Before the step's last unit: every wavefront has read this stage out (its last reads were
+                    // issued a unit ago) and has written its pieces of the next one.
+                    if (last_unit) __syncthreads();
+                    const int nsb = h + 1 < U ? sb : sb + 1, nh = h + 1 < U ? h + 1 : 0;
+                    const int ntiles = h ? NCT - NU0 : NU0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (j < ntiles) {
+                            // the next unit's operand j (the units of a sub-step may differ in size: the rest below)
+                            if (j < (nh ? NCT - NU0 : NU0))
+                                bq[(v + 1) & 1][j] = *(const half8_t*)((last_unit ? nxt : cur) + b_off[nsb & 3] +
+                                                                        (8 * nh + j) * (16 * kRowBytes));
+#pragma unroll
+                            for (int t = 0; t < NA; ++t)
+                                mfma16_tied(acc[t][8 * h + j], __builtin_bit_cast(half8_t, ar[slot][t]), bq[v & 1][j]);
+                            // Activation staging, one piece per group.  One batch per stage: stage step + 1 goes
+                            // to LDS during the first sub-step (the buffer has been free since the last barrier) and
+                            // stage step + 2 takes its place in the registers.  Two batches: the second batch of
+                            // stage step + 1 goes to LDS in unit 2; the first batch of stage step + 2 is loaded in
+                            // unit 3 and written after the barrier, in the last unit, into the stage just read out,
+                            // where the second batch is loaded.
+                            if (U == 1) {
+                                if (v == 0) { store_x1(j, step + 1); load_x1(j, step + 2); }
+                            } else {
+                                if (v == 2 && XB + j < NCT) store_x1(XB + j, step + 1);
+                                if (v == 3) {
+#pragma unroll
+                                    for (int i = j; i < XB; i += ntiles) load_x1(i, step + 2);
+                                }
+                                if (last_unit) {
+#pragma unroll
+                                    for (int i = j; i < XB; i += ntiles) {
+                                        store_x1(i, step + 2);
+                                        if (XB + i < NCT) load_x1(XB + i, step + 2);
+                                    }
+                                }
+                            }
+                            MOEMIX_SB;
+                        }
+                    }
+                    if ((nh ? NCT - NU0 : NU0) > ntiles) {         // operands of the next unit this one had no group for
+#pragma unroll
+                        for (int j = ntiles; j < (nh ? NCT - NU0 : NU0); ++j)
+                            bq[(v + 1) & 1][j] = *(const half8_t*)((last_unit ? nxt : cur) + b_off[nsb & 3] +
+                                                                    (8 * nh + j) * (16 * kRowBytes));
+                        MOEMIX_SB;
                     }
                 }
-            } else {
-                float* y = (float*)out_base + g * N;
-#pragma unroll
-                for (int tile = 0; tile < NA; ++tile) {
-                    const int col = c.n0 + wave * (NT / 4) + tile * 16 + c4 * 4;
-                    if (col < N) *(float4_t*)(y + col) = acc[tile][j];
-                }
+                load_a(slot, 4 * step + sb + R);
+                MOEMIX_SB;
             }
         }
     }
+    mfma_settle();
+    store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
 }
 
 // WIDE: the block holds 8-bit experts as well.  The 8-bit body needs more registers than the other two, and a
@@ -479,28 +661,42 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][SPB * 256 + 16]
     const int tid = threadIdx.x;
 
-    // ---- which expert, which rows
-    int e, begin, cnt, chunk = blockIdx.y;
+    // ---- which expert, which rows.  Chunks hold at most MC rows, those of 16-bit experts in launches with 128-row
+    // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
+    const int n_steps = a.k_per_split / kKTile;
+    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.unit_bytes == 4096;   // (4096: the launch's LDS holds two 256-row stages)
+    auto chunk_rows = [&](int expert, int n) {   // rows per chunk of an expert with n rows
+        if (!(wide_ok && a.ex.e[expert].prec == MOE_PREC_FP16 && n > 16 * (kDirectNCT - 1))) return MC;
+        const int nch = (n + kDirectRows - 1) / kDirectRows;
+        return (((n + nch - 1) / nch) + 15) & ~15;
+    };
+    int e, begin, cnt, per, chunk = blockIdx.y;
     if (a.direct_expert >= 0) {
-        e = a.direct_expert; begin = 0; cnt = a.direct_n;
+        e = a.direct_expert; begin = 0; cnt = a.direct_n; per = chunk_rows(e, cnt);
     } else {
-        e = -1; begin = 0; cnt = 0;
+        e = -1; begin = 0; cnt = 0; per = MC;
         for (int i = 0; i < a.E; ++i) {
-            const int b = a.offsets[i], n = a.offsets[i + 1] - b, nch = (n + MC - 1) / MC;
-            if (chunk < nch) { e = i; begin = b; cnt = n; break; }
+            const int b = a.offsets[i], n = a.offsets[i + 1] - b, pr = chunk_rows(i, n), nch = (n + pr - 1) / pr;
+            if (chunk < nch) { e = i; begin = b; cnt = n; per = pr; break; }
             chunk -= nch;
         }
         if (e < 0) return;
     }
     TileCtx c;
-    c.m0 = chunk * MC;
+    c.m0 = chunk * per;
     if (c.m0 >= cnt) return;
     c.in = a.in; c.perm = a.perm; c.top_k = a.top_k; c.K = a.K; c.N = a.N;
     c.begin = begin;
-    c.rows = min(MC, cnt - c.m0);
+    c.rows = min(per, cnt - c.m0);
     c.n0 = blockIdx.x * NT;
     c.k_begin = blockIdx.z * a.k_per_split;
-    c.n_steps = a.k_per_split / kKTile;
+    c.n_steps = n_steps;
+    // Workgroups that work on different weight rows start at different places of the contraction range and wrap
+    // around: walking it in step, every workgroup of the launch would ask for the same columns of rows that lie a
+    // power of two apart at the same time, which lands on a fraction of the memory channels (measured with a bare
+    // read kernel of the same access pattern: 4.3 TB/s in step, 6.0 TB/s staggered).  The offset depends on the
+    // tile of weight rows only, so a given output element is summed in the same order in every launch shape.
+    c.rot = (c.n_steps & 3) ? 0 : 4 * ((blockIdx.x * 5) % (c.n_steps >> 2));
     c.mc = MC;
     c.unit_bytes = a.unit_bytes;
     c.lds = lds;
@@ -528,6 +724,25 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
         else if (WIDE && prec == MOE_PREC_INT8G64) tile_body<UP, WIDE ? MOE_PREC_INT8G64 : MOE_PREC_FP16, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base); \
         else tile_body<UP, MOE_PREC_FP16, ((n) <= CT ? (n) : CT), SPB, NA>(c, ee, out_base);                    \
     } while (0)
+#define MOEMIX_DIRECT(n) direct_body<UP, CT >= 8 ? (n) : 8>(c, ee, out_base)
+    if (CT >= 8 && wide_ok && prec == MOE_PREC_FP16 && nct >= kDirectNCT) {
+        switch (nct) {
+            case 5: MOEMIX_DIRECT(5); break;
+            case 6: MOEMIX_DIRECT(6); break;
+            case 7: MOEMIX_DIRECT(7); break;
+            case 8: MOEMIX_DIRECT(8); break;
+            case 9: MOEMIX_DIRECT(9); break;
+            case 10: MOEMIX_DIRECT(10); break;
+            case 11: MOEMIX_DIRECT(11); break;
+            case 12: MOEMIX_DIRECT(12); break;
+            case 13: MOEMIX_DIRECT(13); break;
+            case 14: MOEMIX_DIRECT(14); break;
+            case 15: MOEMIX_DIRECT(15); break;
+            default: MOEMIX_DIRECT(16); break;
+        }
+        return;
+    }
+#undef MOEMIX_DIRECT
     if (WIDE) {
         if (CT >= 8 && nct > 4) MOEMIX_BODY(8);
         else if (CT >= 4 && nct > 2) MOEMIX_BODY(4);
