@@ -649,6 +649,192 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
     store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
 }
 
+// 4-bit weights against chunks of 17 .. 128 activation rows (launches with 128-row chunks): the same pinned schedule
+// as direct_body, with the expansion of the codes folded in.  The codes skip LDS too: lane (r16, c4) loads the 16
+// bytes that hold its 32 codes of a 128-column step (16 rows x 64 bytes per instruction) into a ring of R steps;
+// word sb of the 16 bytes is its operand of sub-step sb (columns 32 c4 + 8 sb .. + 7 in the order
+// (0,4,1,5,2,6,3,7), which the staged activations follow).  The A operands of a sub-step are expanded during the
+// products of the sub-step before it, into a second register set; the scales and zeros of a step are fetched with
+// the loads of four steps (lane (r16, c4) fetches the two groups of step 4 S + c4) and handed out through the
+// lane-permute network during the step before (asked for in its first sub-step, picked up in its third).
+// The number of steps is a multiple of 4 here.
+template <bool UP, int NCT>
+__device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
+    constexpr int NA = 4;
+    constexpr int NT = UP ? 32 * NA : 64 * NA;
+    constexpr int R = 4;                               // ring slots = steps of codes in flight
+    constexpr int kRowBytes = kKTile * 2;              // one activation row of a stage: 256 bytes, 16 slots
+    constexpr int kStageBytes = 128 * kRowBytes;
+    const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, c4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = c.K, N = c.N, n_steps = c.n_steps;
+    const int last = n_steps - 1;
+    auto phys_step = [&](int step) {                   // steps past the end repeat the last one
+        step = step < last ? step : last;
+        return step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
+    };
+
+    // ---- activation pieces this thread stages: 16-byte piece tid & 15 of rows (tid >> 4) + 16 i, into slot
+    // (tid & 15) ^ (tid >> 4) of the row, its 8 elements in the order the expanded codes have
+    const gptr_t xbase = scalar_ptr(c.in + c.k_begin);
+    uint32_t xoff[NCT];
+#pragma unroll
+    for (int i = 0; i < NCT; ++i) {
+        int rr = (tid >> 4) + 16 * i;
+        rr = rr < c.rows ? rr : c.rows - 1;
+        const int g = c.begin + c.m0 + rr;
+        const uint32_t src = (UP && c.perm) ? (uint32_t)(c.perm[g] / c.top_k) : (uint32_t)g;
+        xoff[i] = src * (uint32_t)K * 2 + (tid & 15) * 16;
+    }
+    uint4_t xr[NCT];
+    uint8_t* const xst = c.lds + (tid >> 4) * kRowBytes + (((tid & 15) ^ (tid >> 4)) * 16);
+    auto load_x1 = [&](int i, int stage) {
+        xr[i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + xoff[i] + phys_step(stage) * kRowBytes);
+    };
+    auto store_x1 = [&](int i, int stage) {
+        const half8_t h = __builtin_bit_cast(half8_t, xr[i]);
+        *(half8_t*)(xst + (stage & 1) * kStageBytes + i * (16 * kRowBytes)) =
+            half8_t{h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
+    };
+
+    // ---- weights: row r16 of each of the wavefront's NA tiles: codes, scales, zeros
+    gptr_t cbase[NA];
+    uint32_t doff[NA];
+    const half_t* wscale[NA];
+    const half_t* wzero[NA];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
+        const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+        cbase[t] = scalar_ptr(m.data + (c.k_begin >> 1));
+        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
+        row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
+        doff[t] = (uint32_t)row * (uint32_t)(K >> 1) + c4 * 16;
+        wscale[t] = m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6);
+        wzero[t] = m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6);
+    }
+    uint4_t ar[R][NA];
+    auto load_a = [&](int slot, int step) {
+        const int ps = phys_step(step);
+#pragma unroll
+        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + ps * 64);
+    };
+    uint32_t sz_a[NA][2], sz_b[NA][2];                 // scales / zeros of the four steps under way, of the next four
+    auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
+        const int ps = phys_step(4 * S + c4);          // (rotation and range are multiples of 4 steps: no wrap inside)
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            dst[t][0] = *(const uint32_t*)(wscale[t] + ps * 2);
+            dst[t][1] = *(const uint32_t*)(wzero[t] + ps * 2);
+        }
+    };
+    const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
+    const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
+    half2_t s2[NA], z2[NA];
+    uint32_t hs[NA], hz[NA];                           // a step's scale and zero words on their way through the network
+    auto hand_ask = [&](const uint32_t (&src)[NA][2], int g) {
+        const int from = (r16 + 16 * (g & 3)) * 4;     // the lane of this row that fetched step g's scales
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            hs[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][0]);
+            hz[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][1]);
+        }
+    };
+    auto hand_take = [&](half2_t (&so)[NA], half2_t (&zo)[NA]) {
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            so[t] = as_half2(__builtin_amdgcn_perm(hs[t], hs[t], sel));
+            zo[t] = as_half2(__builtin_amdgcn_perm(hz[t], hz[t], sel));
+        }
+    };
+
+    float4_t acc[NA][NCT];
+#pragma unroll
+    for (int t = 0; t < NA; ++t)
+#pragma unroll
+        for (int j = 0; j < NCT; ++j) acc[t][j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // B operand of tile j, sub-step sb: row 16 j + r16, piece 4 c4 + sb, which sits in slot (4 c4 + sb) ^ r16
+    int b_off[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) b_off[sb] = r16 * kRowBytes + (((4 * c4 + sb) ^ r16) * 16);
+    half8_t bq[2][NCT], af[2][NA];
+
+    // stage 0 to LDS, stage 1 in registers; scales of the first four steps; the ring
+#pragma unroll
+    for (int i = 0; i < NCT; ++i) load_x1(i, 0);
+    load_sz(sz_a, 0);
+#pragma unroll
+    for (int i = 0; i < NCT; ++i) { store_x1(i, 0); load_x1(i, 1); }
+    MOEMIX_SB;
+#pragma unroll
+    for (int u = 0; u < R; ++u) load_a(u, u);
+    MOEMIX_SB;
+    hand_ask(sz_a, 0);
+    hand_take(s2, z2);
+#pragma unroll
+    for (int t = 0; t < NA; ++t) af[0][t] = expand_word(ar[0][t][0], s2[t], z2[t], m1024, m64);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NCT; ++j) bq[0][j] = *(const half8_t*)(c.lds + b_off[0] + j * (16 * kRowBytes));
+    MOEMIX_SB;
+
+    for (int base = 0; base < n_steps; base += 4) {
+        load_sz(sz_b, base / 4 + 1);
+        MOEMIX_SB;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int step = base + g;
+            const uint8_t* const cur = c.lds + (step & 1) * kStageBytes;
+            const uint8_t* const nxt = c.lds + ((step + 1) & 1) * kStageBytes;
+            half2_t s2n[NA], z2n[NA];
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                const int u = 4 * g + sb;                          // parity of the B and A register sets
+                if (sb == 3) __syncthreads();                      // stage step + 1 is in LDS, this stage is read out
+                // what the next sub-step multiplies: word sb + 1 of this step's codes, or word 0 of the next step's
+                const int nslot = sb < 3 ? g : (g + 1) & 3, nword = (sb + 1) & 3;
+#pragma unroll
+                for (int j = 0; j < NCT; ++j) {
+                    if (sb == 0) {                                 // stage step + 1 to LDS, stage step + 2 on its way
+                        store_x1(j, step + 1);
+                        load_x1(j, step + 2);
+                    }
+                    bq[(u + 1) & 1][j] = *(const half8_t*)((sb < 3 ? cur : nxt) + b_off[nword] + j * (16 * kRowBytes));
+#pragma unroll
+                    for (int t = 0; t < NA; ++t) mfma16_tied(acc[t][j], af[u & 1][t], bq[u & 1][j]);
+                    // a slice of the work for the next sub-step: its A operands, one tile per group
+#pragma unroll
+                    for (int t = 0; t < NA; ++t)
+                        if (t % NCT == j)
+                            af[(u + 1) & 1][t] = expand_word(ar[nslot][t][nword], sb < 3 ? s2[t] : s2n[t],
+                                                             sb < 3 ? z2[t] : z2n[t], m1024, m64);
+                    MOEMIX_SB;
+                }
+                if (sb == 0) {                                     // the next step's scales and zeros: asked for ...
+                    if (g < 3) hand_ask(sz_a, g + 1);
+                    else hand_ask(sz_b, 0);
+                    MOEMIX_SB;
+                }
+                if (sb == 2) {                                     // ... and picked up two sub-steps later
+                    hand_take(s2n, z2n);
+                    MOEMIX_SB;
+                }
+                if (sb == 3) {                                     // this step's codes are used up
+                    load_a(g, step + R);
+#pragma unroll
+                    for (int t = 0; t < NA; ++t) { s2[t] = s2n[t]; z2[t] = z2n[t]; }
+                    MOEMIX_SB;
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NA; ++t) { sz_a[t][0] = sz_b[t][0]; sz_a[t][1] = sz_b[t][1]; }
+    }
+    mfma_settle();
+    store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
+}
+
 // WIDE: the block holds 8-bit experts as well.  The 8-bit body needs more registers than the other two, and a
 // kernel's register count is that of its largest body, so blocks without 8-bit experts get a kernel without it
 // (and keep four wavefronts per SIMD at few rows per expert).  The wide kernel has bodies for 1, 2, 4 and 8 tiles.
@@ -743,6 +929,20 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
         return;
     }
 #undef MOEMIX_DIRECT
+#define MOEMIX_QUANT4(n) quant4_body<UP, CT >= 8 ? (n) : 8>(c, ee, out_base)
+    if (CT >= 8 && !WIDE && prec == MOE_PREC_INT4G64 && !(n_steps & 3) && nct >= 2) {
+        switch (nct) {
+            case 2: MOEMIX_QUANT4(2); break;
+            case 3: MOEMIX_QUANT4(3); break;
+            case 4: MOEMIX_QUANT4(4); break;
+            case 5: MOEMIX_QUANT4(5); break;
+            case 6: MOEMIX_QUANT4(6); break;
+            case 7: MOEMIX_QUANT4(7); break;
+            default: MOEMIX_QUANT4(8); break;
+        }
+        return;
+    }
+#undef MOEMIX_QUANT4
     if (WIDE) {
         if (CT >= 8 && nct > 4) MOEMIX_BODY(8);
         else if (CT >= 4 && nct > 2) MOEMIX_BODY(4);
