@@ -34,9 +34,6 @@ constexpr int kSPBMax = 2;         // most 128-column steps per LDS stage
 constexpr int spb_for(int ct) { return (8 / ct) < kSPBMax ? (8 / ct) : kSPBMax; }
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
 constexpr int kDirectRows = 256;            // most activation rows of a chunk of a 16-bit expert (direct_body)
-#ifndef MOEMIX_SB
-#define MOEMIX_SB __builtin_amdgcn_sched_barrier(0)
-#endif
 
 struct MfmaArgs {
     DevExperts ex;
@@ -66,6 +63,10 @@ __device__ __forceinline__ gptr_t scalar_ptr(const void* p) {
 __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
+
+// Nothing moves across this point when the compiler schedules instructions: the pipelined bodies below lay out
+// their loads, LDS accesses and products by hand.
+__device__ __forceinline__ void pin_schedule() { __builtin_amdgcn_sched_barrier(0); }
 
 // The same product with the accumulator tied to one register tuple by construction: in long straight-line loops the
 // compiler otherwise unties some products (writes the sum to a new tuple), leaves every accumulator somewhere else
@@ -571,13 +572,13 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
 #pragma unroll
         for (int i = 0; i < XB; ++i) { store_x1(i, 1); if (XB + i < NCT) load_x1(XB + i, 1); }
     }
-    MOEMIX_SB;
+    pin_schedule();
 #pragma unroll
     for (int u = 0; u < R; ++u) load_a(u, u);
-    MOEMIX_SB;
+    pin_schedule();
     __syncthreads();
     read_unit(bq[0], c.lds, 0, 0);
-    MOEMIX_SB;
+    pin_schedule();
 
     for (int base = 0; base < n_steps; base += R / 4) {            // (the number of steps is even here)
 #pragma unroll
@@ -629,7 +630,7 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
                                     }
                                 }
                             }
-                            MOEMIX_SB;
+                            pin_schedule();
                         }
                     }
                     if ((nh ? NCT - NU0 : NU0) > ntiles) {         // operands of the next unit this one had no group for
@@ -637,11 +638,11 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
                         for (int j = ntiles; j < (nh ? NCT - NU0 : NU0); ++j)
                             bq[(v + 1) & 1][j] = *(const half8_t*)((last_unit ? nxt : cur) + b_off[nsb & 3] +
                                                                     (8 * nh + j) * (16 * kRowBytes));
-                        MOEMIX_SB;
+                        pin_schedule();
                     }
                 }
                 load_a(slot, 4 * step + sb + R);
-                MOEMIX_SB;
+                pin_schedule();
             }
         }
     }
@@ -766,10 +767,10 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     load_sz(sz_a, 0);
 #pragma unroll
     for (int i = 0; i < NCT; ++i) { store_x1(i, 0); load_x1(i, 1); }
-    MOEMIX_SB;
+    pin_schedule();
 #pragma unroll
     for (int u = 0; u < R; ++u) load_a(u, u);
-    MOEMIX_SB;
+    pin_schedule();
     hand_ask(sz_a, 0);
     hand_take(s2, z2);
 #pragma unroll
@@ -777,11 +778,11 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NCT; ++j) bq[0][j] = *(const half8_t*)(c.lds + b_off[0] + j * (16 * kRowBytes));
-    MOEMIX_SB;
+    pin_schedule();
 
     for (int base = 0; base < n_steps; base += 4) {
         load_sz(sz_b, base / 4 + 1);
-        MOEMIX_SB;
+        pin_schedule();
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int step = base + g;
@@ -809,22 +810,22 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
                         if (t % NCT == j)
                             af[(u + 1) & 1][t] = expand_word(ar[nslot][t][nword], sb < 3 ? s2[t] : s2n[t],
                                                              sb < 3 ? z2[t] : z2n[t], m1024, m64);
-                    MOEMIX_SB;
+                    pin_schedule();
                 }
                 if (sb == 0) {                                     // the next step's scales and zeros: asked for ...
                     if (g < 3) hand_ask(sz_a, g + 1);
                     else hand_ask(sz_b, 0);
-                    MOEMIX_SB;
+                    pin_schedule();
                 }
                 if (sb == 2) {                                     // ... and picked up two sub-steps later
                     hand_take(s2n, z2n);
-                    MOEMIX_SB;
+                    pin_schedule();
                 }
                 if (sb == 3) {                                     // this step's codes are used up
                     load_a(g, step + R);
 #pragma unroll
                     for (int t = 0; t < NA; ++t) { s2[t] = s2n[t]; z2[t] = z2n[t]; }
-                    MOEMIX_SB;
+                    pin_schedule();
                 }
             }
         }
@@ -1031,10 +1032,15 @@ MfmaPlan plan_mfma(int P, int d, int f, int E) {
     const int steps = f / kKTile;
     const int down_rows = 64 * (p.ct <= 2 ? kNASmall : 4);
     const int base = ((d + down_rows - 1) / down_rows) * (P / (16 * p.ct) + 1);
-    int best = 1;
+    int best = 1, best4 = 0;
     for (int s = 1; s <= 16; ++s)
-        if (steps % s == 0 && steps / s >= 2 && base * s <= 640) best = s;
-    p.down_splits = best;
+        if (steps % s == 0 && steps / s >= 2 && base * s <= 640) {
+            best = s;
+            if ((steps / s) % 4 == 0) best4 = s;
+        }
+    // launches with 128-row chunks have pipelined bodies for ranges of a multiple of 4 steps: a split that gives
+    // such ranges is preferred if it keeps at least half the workgroups
+    p.down_splits = (p.ct == 8 && best4 * 2 >= best) ? best4 : best;
     return p;
 }
 
