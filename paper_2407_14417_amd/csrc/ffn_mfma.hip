@@ -45,6 +45,7 @@ struct MfmaArgs {
     void* out;                // up: h [rows, N] fp16; down: y [splits][rows_total, N] fp32
     int K, N, E;
     int k_per_split;          // contraction elements per split (multiple of 128)
+    int tiles;                // tiles of weight rows (grid.x = tiles * splits)
     size_t split_stride;      // elements of y between two splits
     int unit_bytes;           // LDS bytes per A operand for weight staging: 4096 if any expert is 16-bit, else 2048
     int32_t* status;
@@ -847,6 +848,9 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     constexpr int SPB = spb_for(CT);          // 128-column steps per LDS stage
     extern __shared__ __align__(16) uint8_t lds[];   // [2][MC][SPB * 256 + 16]
     const int tid = threadIdx.x;
+    // grid: x = tile of weight rows + tiles * contraction split, y = chunk: workgroups are handed out chunk by
+    // chunk, in expert order
+    const int tile_x = blockIdx.x % a.tiles, split_z = blockIdx.x / a.tiles;
 
     // ---- which expert, which rows.  Chunks hold at most MC rows, those of 16-bit experts in launches with 128-row
     // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
@@ -875,23 +879,23 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     c.in = a.in; c.perm = a.perm; c.top_k = a.top_k; c.K = a.K; c.N = a.N;
     c.begin = begin;
     c.rows = min(per, cnt - c.m0);
-    c.n0 = blockIdx.x * NT;
-    c.k_begin = blockIdx.z * a.k_per_split;
+    c.n0 = tile_x * NT;
+    c.k_begin = split_z * a.k_per_split;
     c.n_steps = n_steps;
     // Workgroups that work on different weight rows start at different places of the contraction range and wrap
     // around: walking it in step, every workgroup of the launch would ask for the same columns of rows that lie a
     // power of two apart at the same time, which lands on a fraction of the memory channels (measured with a bare
     // read kernel of the same access pattern: 4.3 TB/s in step, 6.0 TB/s staggered).  The offset depends on the
     // tile of weight rows only, so a given output element is summed in the same order in every launch shape.
-    c.rot = (c.n_steps & 3) ? 0 : 4 * ((blockIdx.x * 5) % (c.n_steps >> 2));
+    c.rot = (c.n_steps & 3) ? 0 : 4 * ((tile_x * 5) % (c.n_steps >> 2));
     c.mc = MC;
     c.unit_bytes = a.unit_bytes;
     c.lds = lds;
     const DevExpert& ee = a.ex.e[e];
-    void* out_base = UP ? a.out : (void*)((float*)a.out + blockIdx.z * a.split_stride);
+    void* out_base = UP ? a.out : (void*)((float*)a.out + split_z * a.split_stride);
     if (ee.resident == kDeferred) return;
     if (!(ee.resident && ee.w1.data && ee.w3.data && ee.w2.data)) {
-        if (tid == 0 && blockIdx.x == 0) atomicOr(a.status, kStatusNotResident);
+        if (tid == 0 && tile_x == 0) atomicOr(a.status, kStatusNotResident);
         if (!UP) {   // rows of an expert that cannot run contribute nothing
             float* y = (float*)out_base;
             for (int i = tid; i < c.rows * NT; i += 256) {
@@ -1053,7 +1057,8 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
     const int up_rows = 32 * (ct <= 2 ? kNASmall : 4);
-    dim3 grid((f + up_rows - 1) / up_rows, chunk_slots(rows, P, E, ct), 1);
+    a.tiles = (f + up_rows - 1) / up_rows;
+    dim3 grid(a.tiles, chunk_slots(rows, P, E, ct), 1);
     launch_ct<true>(a, ct, grid, st);
 }
 
@@ -1067,7 +1072,8 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
     const int down_rows = 64 * (ct <= 2 ? kNASmall : 4);
-    dim3 grid((d + down_rows - 1) / down_rows, chunk_slots(rows, P, E, ct), splits);
+    a.tiles = (d + down_rows - 1) / down_rows;
+    dim3 grid(a.tiles * splits, chunk_slots(rows, P, E, ct), 1);
     launch_ct<false>(a, ct, grid, st);
 }
 

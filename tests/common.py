@@ -109,6 +109,10 @@ MEDIUM_ZIPF = Config("medium_zipf", 1024, 2816, 8, 2, 96, (2, 3, 4, 5, 6, 7), zi
 # Shapes that stress the matrix-core path: odd numbers of 128-column steps in both contractions (d = 5 x 128,
 # f = 7 x 128) and a ragged last tile of 256 weight rows in the down-projection (640 = 2 x 256 + 128).
 ODD_STEPS = Config("odd_steps", 640, 896, 8, 2, 40, (0, 3, 4, 6))
+# Contraction ranges of a multiple of four 128-column steps in both projections (d = 8 steps, f = 16 steps, split
+# into ranges of 4 steps): what the pipelined matrix-core bodies for launches with 128-row chunks ask for.
+STEPS4 = Config("steps4", 1024, 2048, 8, 2, 40, (1, 3, 4, 6))
+STEPS4_ZIPF = Config("steps4_zipf", 1024, 2048, 8, 2, 420, (2, 3, 4, 5, 6, 7), zipf=1.2)
 # d and f multiples of 64 but not of 128: served by the shape-agnostic kernels.
 GENERIC = Config("generic", 192, 320, 4, 2, 9, (1, 2))
 # Smallest shape the batch-1 decode kernels take (d and f multiples of 2048), with a precision mix.
