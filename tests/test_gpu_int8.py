@@ -46,6 +46,9 @@ CASES = [
     common.Config("int8_odd_steps", 640, 896, 8, 2, 40, (0, 4), int8_experts=(1, 3, 6)),
     common.Config("int8_generic", 192, 320, 4, 2, 9, (1,), int8_experts=(2,)),
     common.Config("int8_many_rows", 1024, 2048, 4, 2, 300, (), int8_experts=(0, 1, 2, 3)),
+    # launches with 128-row chunks of the kernel variant that holds the 8-bit body: the 16-bit experts (most of the
+    # rows) run the pipelined direct-operand body with chunks of up to 256 rows, the others the plain one
+    common.Config("int8_three_precisions_zipf", 1024, 2048, 8, 2, 420, (2, 3), int8_experts=(4, 5, 6, 7), zipf=1.2),
     common.Config("int8_decode_small", 2048, 4096, 8, 2, 1, (1, 5), int8_experts=(0, 2, 4, 7)),
     common.Config("int8_decode_all", 4096, 2048, 4, 2, 1, (), int8_experts=(0, 1, 2, 3)),
     common.Config("int8_decode_top3", 2048, 6144, 6, 3, 1, (0,), int8_experts=(1, 2, 4)),
@@ -70,7 +73,7 @@ def test_layer_forward_with_8bit_experts(orc, cfg):
         gate = torch.empty((x.shape[0], cfg.k), dtype=torch.float32, device="cuda")
         mm.moe_layer_forward(layer, dev(x), out, ws, idx, gate)
         assert mm.moe_read_status(ws) == 0
-        ref, ref_idx, ref_gate = orc.layer_forward(x, wl.wg, wl.experts, cfg.k)
+        ref, ref_idx, ref_gate = orc.layer_forward(x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
         assert np.array_equal(idx.cpu().numpy(), ref_idx)
         assert np.allclose(gate.cpu().numpy(), ref_gate, rtol=0, atol=GATE_ATOL)
         assert_ffn_close(out.cpu().numpy(), ref, cfg.name)
