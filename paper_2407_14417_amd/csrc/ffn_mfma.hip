@@ -734,10 +734,10 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
     half2_t s2[NA], z2[NA];
     uint32_t hs[NA], hz[NA];                           // a step's scale and zero words on their way through the network
-    auto hand_ask = [&](const uint32_t (&src)[NA][2], int g) {
+    auto hand_ask = [&](const uint32_t (&src)[NA][2], int g, int t0) {   // tiles t0, t0 + 1
         const int from = (r16 + 16 * (g & 3)) * 4;     // the lane of this row that fetched step g's scales
 #pragma unroll
-        for (int t = 0; t < NA; ++t) {
+        for (int t = t0; t < t0 + 2; ++t) {
             hs[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][0]);
             hz[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][1]);
         }
@@ -772,7 +772,8 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
 #pragma unroll
     for (int u = 0; u < R; ++u) load_a(u, u);
     pin_schedule();
-    hand_ask(sz_a, 0);
+    hand_ask(sz_a, 0, 0);
+    hand_ask(sz_a, 0, 2);
     hand_take(s2, z2);
 #pragma unroll
     for (int t = 0; t < NA; ++t) af[0][t] = expand_word(ar[0][t][0], s2[t], z2[t], m1024, m64);
@@ -781,9 +782,15 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     for (int j = 0; j < NCT; ++j) bq[0][j] = *(const half8_t*)(c.lds + b_off[0] + j * (16 * kRowBytes));
     pin_schedule();
 
+    // Two things shape the order of the memory instructions of a step.  A wavefront can have 16 LDS instructions
+    // under way and stalls at the 17th: the step's LDS writes (staged activations) and lane permutes (scales) are
+    // spread over its first three sub-steps instead of standing with the first one's B operand reads.  And loads
+    // retire in the order of their issue: a load of weights (device memory, some 2.4 us under this kernel's own
+    // traffic) holds back the activation loads behind it (L2 hits) that long, so everything that comes from device
+    // memory goes out right after the step's last activation loads, most of a step before the next ones are
+    // waited for.
+    constexpr int PPS = (NCT + 2) / 3;                 // activation pieces staged per sub-step
     for (int base = 0; base < n_steps; base += 4) {
-        load_sz(sz_b, base / 4 + 1);
-        pin_schedule();
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int step = base + g;
@@ -798,9 +805,9 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
                 const int nslot = sb < 3 ? g : (g + 1) & 3, nword = (sb + 1) & 3;
 #pragma unroll
                 for (int j = 0; j < NCT; ++j) {
-                    if (sb == 0) {                                 // stage step + 1 to LDS, stage step + 2 on its way
-                        store_x1(j, step + 1);
-                        load_x1(j, step + 2);
+                    if (sb < 3 && j < PPS && sb * PPS + j < NCT) {   // stage step + 1 to LDS, stage step + 2 on its way
+                        store_x1(sb * PPS + j, step + 1);
+                        load_x1(sb * PPS + j, step + 2);
                     }
                     bq[(u + 1) & 1][j] = *(const half8_t*)((sb < 3 ? cur : nxt) + b_off[nword] + j * (16 * kRowBytes));
 #pragma unroll
@@ -813,17 +820,20 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
                                                              sb < 3 ? z2[t] : z2n[t], m1024, m64);
                     pin_schedule();
                 }
-                if (sb == 0) {                                     // the next step's scales and zeros: asked for ...
-                    if (g < 3) hand_ask(sz_a, g + 1);
-                    else hand_ask(sz_b, 0);
+                if (sb < 2) {                                      // the next step's scales and zeros: asked for ...
+                    if (g < 3) hand_ask(sz_a, g + 1, 2 * sb);
+                    else hand_ask(sz_b, 0, 2 * sb);
                     pin_schedule();
                 }
-                if (sb == 2) {                                     // ... and picked up two sub-steps later
-                    hand_take(s2n, z2n);
+                if (sb == 2) {
+                    hand_take(s2n, z2n);                           // ... and picked up
+                    // the codes of three steps on, into the slot the last step used up (at step 0 this fetches step
+                    // 3 once more); every fourth step the scales and zeros of the next four
+                    load_a((g + 3) & 3, step + R - 1);
+                    if (g == 0) load_sz(sz_b, base / 4 + 1);
                     pin_schedule();
                 }
-                if (sb == 3) {                                     // this step's codes are used up
-                    load_a(g, step + R);
+                if (sb == 3) {
 #pragma unroll
                     for (int t = 0; t < NA; ++t) { s2[t] = s2n[t]; z2[t] = z2n[t]; }
                     pin_schedule();
