@@ -760,7 +760,20 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     int b_off[4];
 #pragma unroll
     for (int sb = 0; sb < 4; ++sb) b_off[sb] = r16 * kRowBytes + (((4 * c4 + sb) ^ r16) * 16);
-    half8_t bq[2][NCT], af[2][NA];
+    half8_t bq[2][NCT];
+    uint32_t af[2][NA][4];                             // A operands as words: codes (0,4) (1,5) (2,6) (3,7) dequantized
+    // The expansion of a sub-step's NA words (see expand_word) as a list of 52 single instructions, stage by stage
+    // over all tiles, so that no instruction stands next to the one it depends on: 4 shifts, 16 mask-and-or into the
+    // mantissa of 1024 or 64, 16 subtractions of that constant, 16 multiply-adds with scale and zero.
+    uint32_t xw8[NA], xq[NA][4];
+    auto expand_op = [&](int k, int slot, int word, uint32_t (&dst)[NA][4], const half2_t (&sc)[NA], const half2_t (&ze)[NA]) {
+        if (k < 4) { xw8[k] = ar[slot][k][word] >> 8; return; }
+        const int t = ((k - 4) & 15) >> 2, q = (k - 4) & 3;
+        const uint32_t magic = (q & 1) ? m64 : m1024;
+        if (k < 20) xq[t][q] = and_or(q >= 2 ? xw8[t] : ar[slot][t][word], (q & 1) ? 0x00F000F0u : 0x000F000Fu, magic);
+        else if (k < 36) xq[t][q] = __builtin_bit_cast(uint32_t, as_half2(xq[t][q]) - as_half2(magic));
+        else dst[t][q] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_half2(xq[t][q]), sc[t], ze[t]));
+    };
 
     // stage 0 to LDS, stage 1 in registers; scales of the first four steps; the ring
 #pragma unroll
@@ -776,7 +789,7 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     hand_ask(sz_a, 0, 2);
     hand_take(s2, z2);
 #pragma unroll
-    for (int t = 0; t < NA; ++t) af[0][t] = expand_word(ar[0][t][0], s2[t], z2[t], m1024, m64);
+    for (int k = 0; k < 52; ++k) expand_op(k, 0, 0, af[0], s2, z2);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NCT; ++j) bq[0][j] = *(const half8_t*)(c.lds + b_off[0] + j * (16 * kRowBytes));
@@ -810,15 +823,26 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
                         load_x1(sb * PPS + j, step + 2);
                     }
                     bq[(u + 1) & 1][j] = *(const half8_t*)((sb < 3 ? cur : nxt) + b_off[nword] + j * (16 * kRowBytes));
+                    // The sub-step's 4 NCT products and, spread evenly between them, the 52 instructions that expand
+                    // the next sub-step's A operands: a product of this wavefront hides one or two vector
+                    // instructions that follow it, a run of products hides nothing and a run of vector instructions
+                    // leaves the matrix cores idle (bare loops: 4 products then 12 vector instructions 30.8 cycles
+                    // per product, one product then 3 vector instructions 23.8).
 #pragma unroll
-                    for (int t = 0; t < NA; ++t) mfma16_tied(acc[t][j], af[u & 1][t], bq[u & 1][j]);
-                    // a slice of the work for the next sub-step: its A operands, one tile per group
+                    for (int t = 0; t < NA; ++t) {
+                        mfma16_tied(acc[t][j],
+                                    __builtin_bit_cast(half8_t, uint4_t{af[u & 1][t][0], af[u & 1][t][1], af[u & 1][t][2],
+                                                                        af[u & 1][t][3]}),
+                                    bq[u & 1][j]);
+                        constexpr int NM = 4 * NCT;                 // products per sub-step
+                        const int m = 4 * j + t;                    // this one
 #pragma unroll
-                    for (int t = 0; t < NA; ++t)
-                        if (t % NCT == j)
-                            af[(u + 1) & 1][t] = expand_word(ar[nslot][t][nword], sb < 3 ? s2[t] : s2n[t],
-                                                             sb < 3 ? z2[t] : z2n[t], m1024, m64);
-                    pin_schedule();
+                        for (int k = (m * 52 + NM - 1) / NM; k < ((m + 1) * 52 + NM - 1) / NM; ++k) {
+                            if (sb < 3) expand_op(k, nslot, nword, af[(u + 1) & 1], s2, z2);
+                            else expand_op(k, nslot, nword, af[(u + 1) & 1], s2n, z2n);
+                        }
+                        pin_schedule();
+                    }
                 }
                 if (sb < 2) {                                      // the next step's scales and zeros: asked for ...
                     if (g < 3) hand_ask(sz_a, g + 1, 2 * sb);
