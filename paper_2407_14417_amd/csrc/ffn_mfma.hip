@@ -48,6 +48,8 @@ struct MfmaArgs {
     int tiles;                // tiles of weight rows (grid.x = tiles * splits)
     size_t split_stride;      // elements of y between two splits
     int unit_bytes;           // LDS bytes per A operand for weight staging: 4096 if any expert is 16-bit, else 2048
+    int in_offsets32;         // the input rows of this launch span less than 4 GB (the pipelined bodies address them
+                              // with 32-bit byte offsets)
     int32_t* status;
 };
 
@@ -889,7 +891,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     // ---- which expert, which rows.  Chunks hold at most MC rows, those of 16-bit experts in launches with 128-row
     // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
     const int n_steps = a.k_per_split / kKTile;
-    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.unit_bytes == 4096;   // (4096: the launch's LDS holds two 256-row stages)
+    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.unit_bytes == 4096 && a.in_offsets32;   // (4096: the launch's LDS holds two 256-row stages)
     auto chunk_rows = [&](int expert, int n) {   // rows per chunk of an expert with n rows
         if (!(wide_ok && a.ex.e[expert].prec == MOE_PREC_FP16 && n > 16 * (kDirectNCT - 1))) return MC;
         const int nch = (n + kDirectRows - 1) / kDirectRows;
@@ -969,7 +971,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     }
 #undef MOEMIX_DIRECT
 #define MOEMIX_QUANT4(n) quant4_body<UP, CT >= 8 ? (n) : 8>(c, ee, out_base)
-    if (CT >= 8 && !WIDE && prec == MOE_PREC_INT4G64 && !(n_steps & 3) && nct >= 2) {
+    if (CT >= 8 && !WIDE && prec == MOE_PREC_INT4G64 && !(n_steps & 3) && nct >= 2 && a.in_offsets32) {
         switch (nct) {
             case 2: MOEMIX_QUANT4(2); break;
             case 3: MOEMIX_QUANT4(3); break;
@@ -1060,7 +1062,10 @@ int chunk_slots(const RowMap& rows, int P, int E, int ct) {
 }  // namespace
 
 // every contraction range must hold at least two 128-column steps (4-bit codes are fetched in pairs of steps)
-bool mfma_shape_ok(int d, int f) { return d % kKTile == 0 && f % kKTile == 0 && d >= 2 * kKTile && f >= 2 * kKTile; }
+// (and a weight matrix spans less than 4 GB: rows are addressed with 32-bit byte offsets from the matrix)
+bool mfma_shape_ok(int d, int f) {
+    return d % kKTile == 0 && f % kKTile == 0 && d >= 2 * kKTile && f >= 2 * kKTile && (uint64_t)d * (uint64_t)f * 2u < (1ull << 32);
+}
 
 MfmaPlan plan_mfma(int P, int d, int f, int E) {
     MfmaPlan p;
@@ -1090,6 +1095,7 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
+    a.in_offsets32 = (uint64_t)P * (uint64_t)d * 2u < (1ull << 32);
     const int up_rows = 32 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (f + up_rows - 1) / up_rows;
     dim3 grid(a.tiles, chunk_slots(rows, P, E, ct), 1);
@@ -1105,6 +1111,7 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
     a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
+    a.in_offsets32 = (uint64_t)P * (uint64_t)f * 2u < (1ull << 32);
     const int down_rows = 64 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (d + down_rows - 1) / down_rows;
     dim3 grid(a.tiles * splits, chunk_slots(rows, P, E, ct), 1);
