@@ -4,17 +4,21 @@
 //   up  : h[r, n] = silu(sum_c W1[n,c] x_r[c]) * (sum_c W3[n,c] x_r[c])      rows r of one expert, grouped order
 //   down: y[s][r, n] = sum_{c in split s} W2[n,c] h[r,c]                      partial sums of the contraction splits
 //
-// One workgroup = 4 wavefronts = one (expert, tile of weight rows, chunk of <= 16*CT activation rows, split).
+// One workgroup = 4 wavefronts = one (expert, tile of weight rows, chunk of activation rows, contraction split).
 // Weights are the A operand of v_mfma_f32_16x16x32_f16: lane (r, c) holds 8 contraction elements of weight row r.
-// They are read from device memory in whole 128-byte lines (8 lanes per row, 8 rows per load instruction, streamed)
-// and turned into operand layout through a small wavefront-private LDS region; reading them directly in operand
-// layout would touch 16 half lines per instruction and leaves the memory pipeline, not the matrix cores, in charge.
-// 4-bit weights travel as codes and are expanded in registers (codes masked into the mantissa of an fp16
-// constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and zero); 8-bit codes
-// likewise, with a byte permute in place of the masks.  Activations
-// are the B operand: a [16*CT, 128*SPB] tile per stage of the contraction, double-buffered in LDS and shared by
-// the 4 wavefronts.  Each lane's 4 accumulators of one 16x16 product are 4 consecutive weight rows of one
-// activation row, so results are stored as 8-byte (fp16) or 16-byte (fp32) pieces.
+// Activations are the B operand, staged in LDS and shared by the 4 wavefronts.  Each lane's 4 accumulators of one
+// 16x16 product are 4 consecutive weight rows of one activation row, so results are stored as 8-byte (fp16) or
+// 16-byte (fp32) pieces.  4-bit weights travel as codes and are expanded in registers (codes masked into the
+// mantissa of an fp16 constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and
+// zero); 8-bit codes likewise, with a byte permute in place of the masks.
+// Three bodies, chosen per chunk:
+//   tile_body    launches with chunks of at most 64 rows, ranges with an odd number of 128-column steps, 8-bit
+//                experts, one-tile chunks.  Weights are read in whole 128-byte lines (8 lanes per row, 8 rows per
+//                load instruction, streamed) and turned into operand layout through a small wavefront-private LDS
+//                region; activations as a [16*CT, 128*SPB] tile per stage, double-buffered, one barrier per stage.
+//   direct_body  16-bit experts in launches with 128-row chunks: weights straight into operand registers, chunks of
+//                up to 256 rows, the order of loads, LDS reads and products pinned by hand.
+//   quant4_body  4-bit experts in those launches: the same schedule with the expansion of the codes folded in.
 #include <atomic>
 
 #include "common.hpp"
