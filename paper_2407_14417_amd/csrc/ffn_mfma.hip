@@ -890,7 +890,19 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     const int tid = threadIdx.x;
     // grid: x = tile of weight rows + tiles * contraction split, y = chunk: workgroups are handed out chunk by
     // chunk, in expert order
-    const int tile_x = blockIdx.x % a.tiles, split_z = blockIdx.x / a.tiles;
+    // Workgroups go to the 8 XCDs (each with an L2 of its own) in turn, in launch order: with 2, 4 or 8 contraction
+    // splits those of one chunk and split, which read the same slice of the activations, get the indices that
+    // land on the same 4, 2 or 1 XCDs.
+    int tile_x, split_z;
+    {
+        const int sp = gridDim.x / a.tiles, i = blockIdx.x, xcd = i & 7, slot = i >> 3;
+        if (sp > 1 && (a.tiles * sp) % 8 == 0 && 8 % sp == 0) {
+            const int q = 8 / sp;                                  // XCDs per split
+            split_z = xcd / q; tile_x = slot * q + xcd % q;
+        } else {
+            tile_x = i % a.tiles; split_z = i / a.tiles;
+        }
+    }
 
     // ---- which expert, which rows.  Chunks hold at most MC rows, those of 16-bit experts in launches with 128-row
     // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
@@ -926,8 +938,13 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     // around: walking it in step, every workgroup of the launch would ask for the same columns of rows that lie a
     // power of two apart at the same time, which lands on a fraction of the memory channels (measured with a bare
     // read kernel of the same access pattern: 4.3 TB/s in step, 6.0 TB/s staggered).  The offset depends on the
-    // tile of weight rows only, so a given output element is summed in the same order in every launch shape.
-    c.rot = (c.n_steps & 3) ? 0 : 4 * ((tile_x * 5) % (c.n_steps >> 2));
+    // tile of weight rows, the expert and the split only, so a given output element is summed in the same order in
+    // every launch shape.
+    // Up-projection: one starting place per tile.  Down-projection (rows 7 x 4 KB apart in the Mixtral shape, less
+    // prone to the effect): one per expert and contraction split, so that the workgroups which share a slice of the
+    // hidden rows walk it in step and find it in L2 (fetched bytes of the prefill down-projection: 1060 MB with one
+    // starting place per tile, 781 MB per slice, 637 MB with the slice's workgroups on two XCDs as well).
+    c.rot = (c.n_steps & 3) ? 0 : 4 * ((UP ? tile_x * 5 : e * 3 + split_z * 5) % (c.n_steps >> 2));
     c.mc = MC;
     c.unit_bytes = a.unit_bytes;
     c.lds = lds;
