@@ -38,6 +38,7 @@ constexpr int kSPBMax = 2;         // most 128-column steps per LDS stage
 constexpr int spb_for(int ct) { return (8 / ct) < kSPBMax ? (8 / ct) : kSPBMax; }
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
 constexpr int kDirectRows = 256;            // most activation rows of a chunk of a 16-bit expert (direct_body)
+constexpr int kQuantRows = 192;             // ... of a 4-bit expert (quant4_wide_body: 12 tiles leave it the registers it needs)
 
 struct MfmaArgs {
     DevExperts ex;
@@ -94,6 +95,13 @@ __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t b
 }
 
 // fp16 pairs (1024, 1024) and (64, 64) held in vector registers (not volatile: identical copies are merged).
+// A 32-bit lane offset as a value the compiler has not seen before: its widening to 64 bits then stays next to the
+// load that uses it (scalar base + 32-bit lane offset in one instruction) instead of being hoisted out of the loop
+// as a register pair per offset.
+__device__ __forceinline__ uint32_t fresh_offset(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
 __device__ __forceinline__ uint32_t vreg_const(uint32_t v) {
     uint32_t m;
     asm("v_mov_b32 %0, %1" : "=v"(m) : "s"(v));
@@ -518,7 +526,7 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
     auto load_x1 = [&](int i, int stage) {             // piece i of the thread, stage `stage` of the contraction
         int phys = stage < last ? stage : last;
         phys = phys + c.rot < n_steps ? phys + c.rot : phys + c.rot - n_steps;
-        xr[i % XB] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + xoff[i] + phys * kRowBytes);
+        xr[i % XB] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + phys * kRowBytes + fresh_offset(xoff[i]));
     };
     auto store_x1 = [&](int i, int stage) {            // ... into LDS buffer stage & 1
         *(uint4_t*)(xst + (stage & 1) * kStageBytes + i * (16 * kRowBytes)) = xr[i % XB];
@@ -541,7 +549,7 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
         sub = sub < last_sub ? sub : last_sub;
         sub = sub + 4 * c.rot <= last_sub ? sub + 4 * c.rot : sub + 4 * c.rot - 4 * n_steps;
 #pragma unroll
-        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + sub * 64);
+        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + sub * 64 + fresh_offset(doff[t]));
     };
 
     float4_t acc[NA][NCT];
@@ -697,7 +705,7 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     uint4_t xr[NCT];
     uint8_t* const xst = c.lds + (tid >> 4) * kRowBytes + (((tid & 15) ^ (tid >> 4)) * 16);
     auto load_x1 = [&](int i, int stage) {
-        xr[i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + xoff[i] + phys_step(stage) * kRowBytes);
+        xr[i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + phys_step(stage) * kRowBytes + fresh_offset(xoff[i]));
     };
     auto store_x1 = [&](int i, int stage) {
         const half8_t h = __builtin_bit_cast(half8_t, xr[i]);
@@ -708,8 +716,8 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     // ---- weights: row r16 of each of the wavefront's NA tiles: codes, scales, zeros
     gptr_t cbase[NA];
     uint32_t doff[NA];
-    const half_t* wscale[NA];
-    const half_t* wzero[NA];
+    gptr_t sbase[NA], zbase[NA];                       // scales and zeros: uniform bases, one lane offset for both
+    uint32_t soff[NA];
 #pragma unroll
     for (int t = 0; t < NA; ++t) {
         const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
@@ -718,22 +726,23 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
         int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
         row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
         doff[t] = (uint32_t)row * (uint32_t)(K >> 1) + c4 * 16;
-        wscale[t] = m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6);
-        wzero[t] = m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6);
+        sbase[t] = scalar_ptr(m.scale + (c.k_begin >> 6));
+        zbase[t] = scalar_ptr(m.zero + (c.k_begin >> 6));
+        soff[t] = (uint32_t)row * (uint32_t)(K >> 6) * 2;
     }
     uint4_t ar[R][NA];
     auto load_a = [&](int slot, int step) {
         const int ps = phys_step(step);
 #pragma unroll
-        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + doff[t] + ps * 64);
+        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + ps * 64 + fresh_offset(doff[t]));
     };
     uint32_t sz_a[NA][2], sz_b[NA][2];                 // scales / zeros of the four steps under way, of the next four
     auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
         const int ps = phys_step(4 * S + c4);          // (rotation and range are multiples of 4 steps: no wrap inside)
 #pragma unroll
         for (int t = 0; t < NA; ++t) {
-            dst[t][0] = *(const uint32_t*)(wscale[t] + ps * 2);
-            dst[t][1] = *(const uint32_t*)(wzero[t] + ps * 2);
+            dst[t][0] = *(const uint32_t MOEMIX_GLOBAL*)(sbase[t] + ps * 4 + fresh_offset(soff[t]));
+            dst[t][1] = *(const uint32_t MOEMIX_GLOBAL*)(zbase[t] + ps * 4 + fresh_offset(soff[t]));
         }
     };
     const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
@@ -877,6 +886,250 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
 }
 
+// 4-bit weights against chunks of 129 .. 192 activation rows (9 .. 12 tiles): quant4_body's expansion and scale
+// hand-out in direct_body's two-unit schedule.  A workgroup's time is 35 us for expanding its 256 x 4096 codes plus
+// 6 us per tile of 16 rows (prefill workload, per-workgroup device clock stamps), so one chunk of 9 tiles costs 89 us
+// where chunks of 8 tiles and 1 tile cost 87 + 49 us.  A sub-step's products run in two units (tiles 0 .. 7, then the
+// rest), each with its own B register set; the 52 instructions that expand the next sub-step's A operands are spread
+// over the products of both.  Activations are staged in two batches of at most 8 pieces per thread, as in direct_body.
+// Codes and scales of later steps are asked for at the end of a step, right after its last activation loads (loads
+// retire in the order of their issue).  The number of steps is a multiple of 4 here.
+template <bool UP, int NCT>
+__device__ __forceinline__ void quant4_wide_body(const TileCtx& c, const DevExpert& ee, void* out_base) {
+    static_assert(NCT > 8 && 16 * NCT <= kQuantRows, "two units of at most 8 tiles");
+    constexpr int NA = 4;
+    constexpr int NT = UP ? 32 * NA : 64 * NA;
+    constexpr int R = 4;                               // ring slots = steps of codes in flight
+    constexpr int NU0 = 8;                             // tiles in a sub-step's first unit; the second holds the rest
+    constexpr int XB = 8;                              // activation pieces per batch (the second holds the rest)
+    static_assert(NCT - XB <= XB, "two batches");
+    constexpr int kRowBytes = kKTile * 2;              // one activation row of a stage: 256 bytes, 16 slots
+    constexpr int kStageBytes = kDirectRows * kRowBytes;
+    const int tid = threadIdx.x, lane = tid & 63, r16 = lane & 15, c4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = c.K, N = c.N, n_steps = c.n_steps;
+    const int last = n_steps - 1;
+    auto phys_step = [&](int step) {                   // steps past the end repeat the last one
+        step = step < last ? step : last;
+        return step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
+    };
+
+    // ---- activation pieces this thread stages (see quant4_body), at most XB of them in registers at a time
+    const gptr_t xbase = scalar_ptr(c.in + c.k_begin);
+    uint32_t xoff[NCT];
+#pragma unroll
+    for (int i = 0; i < NCT; ++i) {
+        int rr = (tid >> 4) + 16 * i;
+        rr = rr < c.rows ? rr : c.rows - 1;
+        const int g = c.begin + c.m0 + rr;
+        const uint32_t src = (UP && c.perm) ? (uint32_t)(c.perm[g] / c.top_k) : (uint32_t)g;
+        xoff[i] = src * (uint32_t)K * 2 + (tid & 15) * 16;
+    }
+    uint4_t xr[XB];
+    uint8_t* const xst = c.lds + (tid >> 4) * kRowBytes + (((tid & 15) ^ (tid >> 4)) * 16);
+    auto load_x1 = [&](int i, int stage) {
+        xr[i % XB] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + phys_step(stage) * kRowBytes + fresh_offset(xoff[i]));
+    };
+    auto store_x1 = [&](int i, int stage) {
+        const half8_t h = __builtin_bit_cast(half8_t, xr[i % XB]);
+        *(half8_t*)(xst + (stage & 1) * kStageBytes + i * (16 * kRowBytes)) =
+            half8_t{h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
+    };
+
+    // ---- weights: row r16 of each of the wavefront's NA tiles: codes, scales, zeros
+    gptr_t cbase[NA];
+    uint32_t doff[NA];
+    gptr_t sbase[NA], zbase[NA];                       // scales and zeros: uniform bases, one lane offset for both
+    uint32_t soff[NA];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) {
+        const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
+        const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
+        cbase[t] = scalar_ptr(m.data + (c.k_begin >> 1));
+        int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
+        row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
+        doff[t] = (uint32_t)row * (uint32_t)(K >> 1) + c4 * 16;
+        sbase[t] = scalar_ptr(m.scale + (c.k_begin >> 6));
+        zbase[t] = scalar_ptr(m.zero + (c.k_begin >> 6));
+        soff[t] = (uint32_t)row * (uint32_t)(K >> 6) * 2;
+    }
+    uint4_t ar[R][NA];
+    auto load_a = [&](int slot, int step) {
+        const int ps = phys_step(step);
+#pragma unroll
+        for (int t = 0; t < NA; ++t) ar[slot][t] = *(const uint4_t MOEMIX_GLOBAL*)(cbase[t] + ps * 64 + fresh_offset(doff[t]));
+    };
+    uint32_t sz_a[NA][2], sz_b[NA][2];                 // scales / zeros of the four steps under way, of the next four
+    auto load_sz = [&](uint32_t (&dst)[NA][2], int S) {
+        const int ps = phys_step(4 * S + c4);          // (rotation and range are multiples of 4 steps: no wrap inside)
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            dst[t][0] = *(const uint32_t MOEMIX_GLOBAL*)(sbase[t] + ps * 4 + fresh_offset(soff[t]));
+            dst[t][1] = *(const uint32_t MOEMIX_GLOBAL*)(zbase[t] + ps * 4 + fresh_offset(soff[t]));
+        }
+    };
+    const uint32_t sel = (c4 >> 1) ? 0x03020302u : 0x01000100u;   // which of the two groups of a 128-column step
+    const uint32_t m1024 = vreg_const(0x64006400u), m64 = vreg_const(0x54005400u);
+    half2_t s2[NA], z2[NA];
+    uint32_t hs[NA], hz[NA];
+    auto hand_ask = [&](const uint32_t (&src)[NA][2], int g, int t0) {   // tiles t0, t0 + 1
+        const int from = (r16 + 16 * (g & 3)) * 4;
+#pragma unroll
+        for (int t = t0; t < t0 + 2; ++t) {
+            hs[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][0]);
+            hz[t] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)src[t][1]);
+        }
+    };
+    auto hand_take = [&](half2_t (&so)[NA], half2_t (&zo)[NA]) {
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            so[t] = as_half2(__builtin_amdgcn_perm(hs[t], hs[t], sel));
+            zo[t] = as_half2(__builtin_amdgcn_perm(hz[t], hz[t], sel));
+        }
+    };
+
+    float4_t acc[NA][NCT];
+#pragma unroll
+    for (int t = 0; t < NA; ++t)
+#pragma unroll
+        for (int j = 0; j < NCT; ++j) acc[t][j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // B operand of tile j, sub-step sb: row 16 j + r16, piece 4 c4 + sb, which sits in slot (4 c4 + sb) ^ r16
+    int b_off[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) b_off[sb] = r16 * kRowBytes + (((4 * c4 + sb) ^ r16) * 16);
+    half8_t bq[2][8];
+    uint32_t af[2][NA][4];
+    uint32_t xw8[NA];
+    // the 52 instructions of quant4_body's expansion; the intermediate values live in the destination registers
+    auto expand_op = [&](int k, int slot, int word, uint32_t (&dst)[NA][4], const half2_t (&sc)[NA], const half2_t (&ze)[NA]) {
+        if (k < 4) { xw8[k] = ar[slot][k][word] >> 8; return; }
+        const int t = ((k - 4) & 15) >> 2, q = (k - 4) & 3;
+        const uint32_t magic = (q & 1) ? m64 : m1024;
+        if (k < 20) dst[t][q] = and_or(q >= 2 ? xw8[t] : ar[slot][t][word], (q & 1) ? 0x00F000F0u : 0x000F000Fu, magic);
+        else if (k < 36) dst[t][q] = __builtin_bit_cast(uint32_t, as_half2(dst[t][q]) - as_half2(magic));
+        else dst[t][q] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_half2(dst[t][q]), sc[t], ze[t]));
+    };
+
+    // Both batches of stage 0 and the first of stage 1 go to LDS here; the second batch of stage 1 is in registers
+    // when the loop starts.  Scales of the first four steps; the ring.
+#pragma unroll
+    for (int i = 0; i < XB; ++i) load_x1(i, 0);
+    load_sz(sz_a, 0);
+#pragma unroll
+    for (int i = 0; i < XB; ++i) { store_x1(i, 0); if (XB + i < NCT) load_x1(XB + i, 0); }
+#pragma unroll
+    for (int i = 0; i < XB; ++i) { if (XB + i < NCT) store_x1(XB + i, 0); load_x1(i, 1); }
+#pragma unroll
+    for (int i = 0; i < XB; ++i) { store_x1(i, 1); if (XB + i < NCT) load_x1(XB + i, 1); }
+    pin_schedule();
+#pragma unroll
+    for (int u = 0; u < R; ++u) load_a(u, u);
+    pin_schedule();
+    hand_ask(sz_a, 0, 0);
+    hand_ask(sz_a, 0, 2);
+    hand_take(s2, z2);
+#pragma unroll
+    for (int k = 0; k < 52; ++k) expand_op(k, 0, 0, af[0], s2, z2);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NU0; ++j) bq[0][j] = *(const half8_t*)(c.lds + b_off[0] + j * (16 * kRowBytes));
+    pin_schedule();
+
+    for (int base = 0; base < n_steps; base += 4) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int step = base + g;
+            const uint8_t* const cur = c.lds + (step & 1) * kStageBytes;
+            const uint8_t* const nxt = c.lds + ((step + 1) & 1) * kStageBytes;
+            half2_t s2n[NA], z2n[NA];
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                const int u = 4 * g + sb;                          // parity of the A register sets
+                // what the next sub-step multiplies: word sb + 1 of this step's codes, or word 0 of the next step's
+                const int nslot = sb < 3 ? g : (g + 1) & 3, nword = (sb + 1) & 3;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int v = 2 * sb + h;                      // unit of the step; B register set v & 1
+                    const bool last_unit = v == 7;
+                    // Before the step's last unit: every wavefront has read this stage out (its last reads were
+                    // issued a unit ago) and has written its pieces of the next one.
+                    if (last_unit) __syncthreads();
+                    const int nh = 1 - h;
+                    const int ntiles = h ? NCT - NU0 : NU0, next_tiles = nh ? NCT - NU0 : NU0;
+                    // the next unit's operands: the same sub-step's second unit, or the next sub-step's first
+                    const uint8_t* const nb = (last_unit ? nxt : cur) + b_off[h ? nword : sb] + 8 * nh * (16 * kRowBytes);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (j < ntiles) {
+                            if (j < next_tiles) bq[(v + 1) & 1][j] = *(const half8_t*)(nb + j * (16 * kRowBytes));
+#pragma unroll
+                            for (int t = 0; t < NA; ++t) {
+                                mfma16_tied(acc[t][8 * h + j],
+                                            __builtin_bit_cast(half8_t, uint4_t{af[u & 1][t][0], af[u & 1][t][1],
+                                                                                af[u & 1][t][2], af[u & 1][t][3]}),
+                                            bq[v & 1][j]);
+                                constexpr int NM = 4 * NCT;         // products per sub-step
+                                const int m = 4 * (8 * h + j) + t;  // this one
+#pragma unroll
+                                for (int k = (m * 52 + NM - 1) / NM; k < ((m + 1) * 52 + NM - 1) / NM; ++k) {
+                                    if (sb < 3) expand_op(k, nslot, nword, af[(u + 1) & 1], s2, z2);
+                                    else expand_op(k, nslot, nword, af[(u + 1) & 1], s2n, z2n);
+                                }
+                                pin_schedule();
+                            }
+                            // Activation staging, one piece per group (direct_body's two-batch order): the second
+                            // batch of stage step + 1 goes to LDS in unit 2; the first batch of stage step + 2 is
+                            // loaded in unit 3 and written after the barrier, in the last unit, into the stage just
+                            // read out, where the second batch is loaded.
+                            if (v == 2 && XB + j < NCT) store_x1(XB + j, step + 1);
+                            if (v == 3) {
+#pragma unroll
+                                for (int i = j; i < XB; i += ntiles) load_x1(i, step + 2);
+                            }
+                            if (last_unit) {
+#pragma unroll
+                                for (int i = j; i < XB; i += ntiles) {
+                                    store_x1(i, step + 2);
+                                    if (XB + i < NCT) load_x1(XB + i, step + 2);
+                                }
+                            }
+                            pin_schedule();
+                        }
+                    }
+                    if (next_tiles > ntiles) {                     // operands of the next unit this one had no group for
+#pragma unroll
+                        for (int j = ntiles; j < next_tiles; ++j) bq[(v + 1) & 1][j] = *(const half8_t*)(nb + j * (16 * kRowBytes));
+                        pin_schedule();
+                    }
+                }
+                if (sb < 2) {                                      // the next step's scales and zeros: asked for ...
+                    if (g < 3) hand_ask(sz_a, g + 1, 2 * sb);
+                    else hand_ask(sz_b, 0, 2 * sb);
+                    pin_schedule();
+                }
+                if (sb == 2) {
+                    hand_take(s2n, z2n);                           // ... and picked up
+                    pin_schedule();
+                }
+                if (sb == 3) {
+                    // the codes of four steps on, into the slot this step has used up; every fourth step the scales
+                    // and zeros of the next four
+                    load_a(g, step + R);
+                    if (g == 0) load_sz(sz_b, base / 4 + 1);
+#pragma unroll
+                    for (int t = 0; t < NA; ++t) { s2[t] = s2n[t]; z2[t] = z2n[t]; }
+                    pin_schedule();
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NA; ++t) { sz_a[t][0] = sz_b[t][0]; sz_a[t][1] = sz_b[t][1]; }
+    }
+    mfma_settle();
+    store_results<UP, NCT, NA>(c, acc, out_base, wave, r16, c4);
+}
+
 // WIDE: the block holds 8-bit experts as well.  The 8-bit body needs more registers than the other two, and a
 // kernel's register count is that of its largest body, so blocks without 8-bit experts get a kernel without it
 // (and keep four wavefronts per SIMD at few rows per expert).  The wide kernel has bodies for 1, 2, 4 and 8 tiles.
@@ -907,10 +1160,16 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     // ---- which expert, which rows.  Chunks hold at most MC rows, those of 16-bit experts in launches with 128-row
     // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
     const int n_steps = a.k_per_split / kKTile;
-    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.unit_bytes == 4096 && a.in_offsets32;   // (4096: the launch's LDS holds two 256-row stages)
+    // (launches with 128-row chunks have LDS for two 256-row stages)
+    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.in_offsets32;
+    const bool wide4_ok = wide_ok && !WIDE && !(n_steps & 3);
     auto chunk_rows = [&](int expert, int n) {   // rows per chunk of an expert with n rows
-        if (!(wide_ok && a.ex.e[expert].prec == MOE_PREC_FP16 && n > 16 * (kDirectNCT - 1))) return MC;
-        const int nch = (n + kDirectRows - 1) / kDirectRows;
+        const int prec = a.ex.e[expert].prec;
+        if (!((wide_ok && prec == MOE_PREC_FP16 && n > 16 * (kDirectNCT - 1)) ||
+              (wide4_ok && prec == MOE_PREC_INT4G64 && n > MC)))
+            return MC;
+        const int cap = prec == MOE_PREC_FP16 ? kDirectRows : kQuantRows;
+        const int nch = (n + cap - 1) / cap;
         return (((n + nch - 1) / nch) + 15) & ~15;
     };
     int e, begin, cnt, per, chunk = blockIdx.y;
@@ -992,7 +1251,8 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     }
 #undef MOEMIX_DIRECT
 #define MOEMIX_QUANT4(n) quant4_body<UP, CT >= 8 ? (n) : 8>(c, ee, out_base)
-    if (CT >= 8 && !WIDE && prec == MOE_PREC_INT4G64 && !(n_steps & 3) && nct >= 2 && a.in_offsets32) {
+#define MOEMIX_QUANT4W(n) quant4_wide_body<UP, CT >= 8 ? (n) : 12>(c, ee, out_base)
+    if (wide4_ok && prec == MOE_PREC_INT4G64 && nct >= 2) {
         switch (nct) {
             case 2: MOEMIX_QUANT4(2); break;
             case 3: MOEMIX_QUANT4(3); break;
@@ -1000,11 +1260,16 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
             case 5: MOEMIX_QUANT4(5); break;
             case 6: MOEMIX_QUANT4(6); break;
             case 7: MOEMIX_QUANT4(7); break;
-            default: MOEMIX_QUANT4(8); break;
+            case 8: MOEMIX_QUANT4(8); break;
+            case 9: MOEMIX_QUANT4W(9); break;
+            case 10: MOEMIX_QUANT4W(10); break;
+            case 11: MOEMIX_QUANT4W(11); break;
+            default: MOEMIX_QUANT4W(12); break;
         }
         return;
     }
 #undef MOEMIX_QUANT4
+#undef MOEMIX_QUANT4W
     if (WIDE) {
         if (CT >= 8 && nct > 4) MOEMIX_BODY(8);
         else if (CT >= 4 && nct > 2) MOEMIX_BODY(4);
@@ -1026,8 +1291,11 @@ template <bool UP, int CT, bool WIDE>
 void launch_one(const MfmaArgs& a, dim3 grid, hipStream_t st) {
     constexpr int NA = CT <= 2 ? kNASmall : 4;
     // activation stages + 4 wavefronts x NA operands of weight staging
+    // (launches with 128-row chunks: at least two unpadded 256-row stages for the pipelined bodies)
+    constexpr size_t lds_wide = CT >= 8 ? 2u * kDirectRows * kKTile * 2 : 0;
     const size_t lds_max = 2u * 16 * CT * (spb_for(CT) * kKTile * 2 + 16) + 4 * NA * 4096;
-    const size_t lds_bytes = 2u * 16 * CT * (spb_for(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
+    const size_t lds_plain = 2u * 16 * CT * (spb_for(CT) * kKTile * 2 + 16) + 4 * NA * (size_t)a.unit_bytes;
+    const size_t lds_bytes = lds_plain > lds_wide ? lds_plain : lds_wide;
     // the attribute belongs to (kernel, device): set it once per device of the process (bit d of the mask; devices
     // past the 64th set it on every launch)
     static std::atomic<unsigned long long> configured{0};
