@@ -11,14 +11,16 @@
 // 16-byte (fp32) pieces.  4-bit weights travel as codes and are expanded in registers (codes masked into the
 // mantissa of an fp16 constant, the constant subtracted, one packed fp16 multiply-add with the group's scale and
 // zero); 8-bit codes likewise, with a byte permute in place of the masks.
-// Three bodies, chosen per chunk:
+// Four bodies, chosen per chunk:
 //   tile_body    launches with chunks of at most 64 rows, ranges with an odd number of 128-column steps, 8-bit
 //                experts, one-tile chunks.  Weights are read in whole 128-byte lines (8 lanes per row, 8 rows per
 //                load instruction, streamed) and turned into operand layout through a small wavefront-private LDS
 //                region; activations as a [16*CT, 128*SPB] tile per stage, double-buffered, one barrier per stage.
 //   direct_body  16-bit experts in launches with 128-row chunks: weights straight into operand registers, chunks of
 //                up to 256 rows, the order of loads, LDS reads and products pinned by hand.
-//   quant4_body  4-bit experts in those launches: the same schedule with the expansion of the codes folded in.
+//   quant4_body  4-bit experts in those launches, chunks of 2 .. 8 tiles: the same schedule with the expansion of the
+//                codes folded in.
+//   quant4_wide_body  the same for chunks of 9 .. 12 tiles (a 4-bit expert's chunks hold up to 192 rows).
 #include <atomic>
 
 #include "common.hpp"

@@ -113,6 +113,9 @@ ODD_STEPS = Config("odd_steps", 640, 896, 8, 2, 40, (0, 3, 4, 6))
 # into ranges of 4 steps): what the pipelined matrix-core bodies for launches with 128-row chunks ask for.
 STEPS4 = Config("steps4", 1024, 2048, 8, 2, 40, (1, 3, 4, 6))
 STEPS4_ZIPF = Config("steps4_zipf", 1024, 2048, 8, 2, 420, (2, 3, 4, 5, 6, 7), zipf=1.2)
+# The same with the 4-bit experts in front: experts 0 and 1 get 391 and 250 of the 840 rows, which run in chunks of 9
+# and 8 tiles (a 4-bit expert's chunks hold up to 192 rows, split evenly), expert 2 in one of 7.
+STEPS4_ZIPF_Q = Config("steps4_zipf_4bit_heavy", 1024, 2048, 8, 2, 420, (0, 1, 2, 4, 5), zipf=1.2)
 # d and f multiples of 64 but not of 128: served by the shape-agnostic kernels.
 GENERIC = Config("generic", 192, 320, 4, 2, 9, (1, 2))
 # Smallest shape the batch-1 decode kernels take (d and f multiples of 2048), with a precision mix.

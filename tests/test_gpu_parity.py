@@ -9,7 +9,8 @@ torch = pytest.importorskip("torch")
 from paper_2407_14417_amd import binding as mm
 from paper_2407_14417_amd import synth
 from tests import common
-from tests.common import TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, build_workload, assert_ffn_close
+from tests.common import (TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q, build_workload,
+                          assert_ffn_close)
 from tests.gpu_common import dev, device_layer, device_mat
 
 pytestmark = pytest.mark.gpu
@@ -208,8 +209,8 @@ def test_expert_ffn_odd_steps_ragged_tiles_many_chunks(orc, n):
 def test_expert_ffn_pipelined_bodies(orc, n):
     """Matrix-core path, launches with 128-row chunks and ranges of a multiple of four steps: the pipelined bodies.
     A 16-bit expert's chunks hold up to 256 rows, split evenly (70 .. 256 rows: one chunk of 5 .. 16 tiles; 257, 300,
-    400: two chunks; 520: three); a 4-bit expert's hold 128 (bodies for 2 .. 8 tiles: 148 = 128 + 20 rows, 188 =
-    128 + 60, 90, 200 = 128 + 72, ...; a last chunk of one tile runs the plain body)."""
+    400: two chunks; 520: three); a 4-bit expert's up to 192 (70 .. 128 rows: one chunk of 5 .. 8 tiles; 129, 148, 188:
+    one of 9, 10, 12 tiles on the two-unit body; 200 .. 300: two chunks of 7 .. 10 tiles; 400, 520: three of 9 and 11)."""
     cfg = STEPS4
     wl = build_workload(cfg, orc, experts_needed=(0, 1))
     assert not wl.experts[0].int4 and wl.experts[1].int4
@@ -287,7 +288,8 @@ def _run_layer(layer, x_np, cfg):
     return out.cpu().numpy(), idx.cpu().numpy(), gate.cpu().numpy(), mm.moe_read_status(ws)
 
 
-@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q],
+                         ids=lambda c: c.name)
 def test_layer_forward(orc, cfg):
     wl = build_workload(cfg, orc)
     _say(f"layer_forward cfg={cfg.name}")

@@ -7,7 +7,7 @@ torch = pytest.importorskip("torch")
 
 from paper_2407_14417_amd import binding as mm
 from tests import common
-from tests.common import TINY, MEDIUM, STEPS4_ZIPF, DECODE_SMALL, build_workload, assert_ffn_close
+from tests.common import TINY, MEDIUM, STEPS4_ZIPF, STEPS4_ZIPF_Q, DECODE_SMALL, build_workload, assert_ffn_close
 from tests.gpu_common import dev, device_layer, device_layer_with_offloaded
 
 pytestmark = pytest.mark.gpu
@@ -27,8 +27,9 @@ def _forward(layer, x, cfg):
 
 
 # (STEPS4_ZIPF: launches with 128-row chunks; the 16-bit experts 0 and 1 hold most rows and run in chunks of up to
-# 256 rows on the pipelined bodies, whether they are resident or come through the swap space)
-@pytest.mark.parametrize("cfg", [TINY, MEDIUM, STEPS4_ZIPF], ids=lambda c: c.name)
+# 256 rows on the pipelined bodies, whether they are resident or come through the swap space; STEPS4_ZIPF_Q: the same
+# for 4-bit experts in chunks of 9 tiles)
+@pytest.mark.parametrize("cfg", [TINY, MEDIUM, STEPS4_ZIPF, STEPS4_ZIPF_Q], ids=lambda c: c.name)
 @pytest.mark.parametrize("offloaded,n_slots", [((0, 3), 1), ((0, 3), 2), ((1, 2, 3), 2), ((0, 1, 2, 3), 4), ((), 1)])
 def test_swap_many_tokens_equals_all_resident_bit_for_bit(orc, cfg, offloaded, n_slots):
     wl = build_workload(cfg, orc)
