@@ -40,6 +40,7 @@ constexpr int kSPBMax = 2;         // most 128-column steps per LDS stage
 constexpr int spb_for(int ct) { return (8 / ct) < kSPBMax ? (8 / ct) : kSPBMax; }
 constexpr int kKTile = 128;                 // contraction elements per LDS tile
 constexpr int kDirectRows = 256;            // most activation rows of a chunk of a 16-bit expert (direct_body)
+constexpr unsigned kComputeUnits = 256;     // of the MI355X
 constexpr int kQuantRows = 192;             // ... of a 4-bit expert (quant4_wide_body: 12 tiles leave it the registers it needs)
 
 struct MfmaArgs {
@@ -1164,7 +1165,11 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     const int n_steps = a.k_per_split / kKTile;
     // (launches with 128-row chunks have LDS for two 256-row stages)
     const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.in_offsets32;
-    const bool wide4_ok = wide_ok && !WIDE && !(n_steps & 3);
+    // (4-bit chunks of more than 128 rows save compute-unit time, not latency: one expert alone whose launch does not
+    // fill the chip twice over is faster with more, smaller workgroups side by side -- 148 rows: 73 us in chunks of
+    // 128 + 20 rows, 89 us in one chunk)
+    const bool quant4_ok = wide_ok && !WIDE && !(n_steps & 3);
+    const bool wide4_ok = quant4_ok && (a.direct_expert < 0 || gridDim.x * gridDim.y >= 2 * kComputeUnits);
     auto chunk_rows = [&](int expert, int n) {   // rows per chunk of an expert with n rows
         const int prec = a.ex.e[expert].prec;
         if (!((wide_ok && prec == MOE_PREC_FP16 && n > 16 * (kDirectNCT - 1)) ||
@@ -1254,7 +1259,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
 #undef MOEMIX_DIRECT
 #define MOEMIX_QUANT4(n) quant4_body<UP, CT >= 8 ? (n) : 8>(c, ee, out_base)
 #define MOEMIX_QUANT4W(n) quant4_wide_body<UP, CT >= 8 ? (n) : 12>(c, ee, out_base)
-    if (wide4_ok && prec == MOE_PREC_INT4G64 && nct >= 2) {
+    if (quant4_ok && prec == MOE_PREC_INT4G64 && nct >= 2) {
         switch (nct) {
             case 2: MOEMIX_QUANT4(2); break;
             case 3: MOEMIX_QUANT4(3); break;

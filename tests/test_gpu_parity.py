@@ -209,8 +209,9 @@ def test_expert_ffn_odd_steps_ragged_tiles_many_chunks(orc, n):
 def test_expert_ffn_pipelined_bodies(orc, n):
     """Matrix-core path, launches with 128-row chunks and ranges of a multiple of four steps: the pipelined bodies.
     A 16-bit expert's chunks hold up to 256 rows, split evenly (70 .. 256 rows: one chunk of 5 .. 16 tiles; 257, 300,
-    400: two chunks; 520: three); a 4-bit expert's up to 192 (70 .. 128 rows: one chunk of 5 .. 8 tiles; 129, 148, 188:
-    one of 9, 10, 12 tiles on the two-unit body; 200 .. 300: two chunks of 7 .. 10 tiles; 400, 520: three of 9 and 11)."""
+    400: two chunks; 520: three); a 4-bit expert alone, in a launch this small, runs in chunks of 128 rows (bodies for
+    2 .. 8 tiles: 148 = 128 + 20 rows, 188 = 128 + 60, 90, 200 = 128 + 72, ...; a last chunk of one tile runs the plain
+    body); its chunks of up to 192 rows are covered by test_layer_forward_4bit_chunks_of_9_to_12_tiles."""
     cfg = STEPS4
     wl = build_workload(cfg, orc, experts_needed=(0, 1))
     assert not wl.experts[0].int4 and wl.experts[1].int4
@@ -295,6 +296,29 @@ def test_layer_forward(orc, cfg):
     _say(f"layer_forward cfg={cfg.name}")
     out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
     ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    assert status == 0
+    assert np.array_equal(idx, ref_idx)
+    assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
+    assert_ffn_close(out, ref, cfg.name)
+
+
+@pytest.mark.parametrize("T,tiles", [(288, (9, 8, 11)), (320, (10, 9, 12)), (360, (11, 10, 7, 7))])
+def test_layer_forward_4bit_chunks_of_9_to_12_tiles(orc, T, tiles):
+    """The busiest 4-bit experts get between 129 and 384 rows: chunks of up to 192 rows, split evenly, on the two-unit
+    body (``tiles``: 16-row tiles of the chunks of experts 0 and 1, as the row counts asserted below imply)."""
+    cfg = common.Config(f"steps4_zipf_4bit_heavy_T{T}", 1024, 2048, 8, 2, T, STEPS4_ZIPF_Q.int4_experts, zipf=1.2)
+    wl = build_workload(cfg, orc)
+    _say(f"layer_forward cfg={cfg.name}")
+    out, idx, gate, status = _run_layer(device_layer(wl), wl.x, cfg)
+    ref, ref_idx, ref_gate = orc.layer_forward(wl.x, wl.wg, wl.experts, cfg.k, bias=wl.bias)
+    counts = np.bincount(ref_idx.reshape(-1), minlength=cfg.E)
+    _say(f"rows per expert: {counts.tolist()}")
+
+    def chunk_tiles(n):          # the library's rule for a 4-bit expert with more than 128 rows
+        nch = -(-n // 192)
+        per = (-(-n // nch) + 15) // 16 * 16
+        return tuple((min(per, n - i * per) + 15) // 16 for i in range(nch))
+    assert chunk_tiles(int(counts[0])) + chunk_tiles(int(counts[1])) == tiles
     assert status == 0
     assert np.array_equal(idx, ref_idx)
     assert np.allclose(gate, ref_gate, rtol=0, atol=GATE_ATOL)
