@@ -58,6 +58,7 @@ struct MfmaArgs {
     int unit_bytes;           // LDS bytes per A operand for weight staging: 4096 if any expert is 16-bit, else 2048
     int in_offsets32;         // the input rows of this launch span less than 4 GB (the pipelined bodies address them
                               // with 32-bit byte offsets)
+    uint8_t order[MOE_MAX_EXPERTS];   // the experts in the order their chunks are handed out
     int32_t* status;
 };
 
@@ -1168,7 +1169,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     // (4-bit chunks of more than 128 rows save compute-unit time, not latency: one expert alone whose launch does not
     // fill the chip twice over is faster with more, smaller workgroups side by side -- 148 rows: 73 us in chunks of
     // 128 + 20 rows, 89 us in one chunk)
-    const bool quant4_ok = wide_ok && !WIDE && !(n_steps & 3);
+    const bool quant4_ok = wide_ok && !(n_steps & 3);
     const bool wide4_ok = quant4_ok && (a.direct_expert < 0 || gridDim.x * gridDim.y >= 2 * kComputeUnits);
     auto chunk_rows = [&](int expert, int n) {   // rows per chunk of an expert with n rows
         const int prec = a.ex.e[expert].prec;
@@ -1183,8 +1184,10 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     if (a.direct_expert >= 0) {
         e = a.direct_expert; begin = 0; cnt = a.direct_n; per = chunk_rows(e, cnt);
     } else {
+        // Chunks are handed out expert by expert in the order the host has put the experts in (launch_order)
         e = -1; begin = 0; cnt = 0; per = MC;
-        for (int i = 0; i < a.E; ++i) {
+        for (int j = 0; j < a.E; ++j) {
+            const int i = a.order[j];
             const int b = a.offsets[i], n = a.offsets[i + 1] - b, pr = chunk_rows(i, n), nch = (n + pr - 1) / pr;
             if (chunk < nch) { e = i; begin = b; cnt = n; per = pr; break; }
             chunk -= nch;
@@ -1327,6 +1330,17 @@ void launch_ct_w(const MfmaArgs& a, int ct, dim3 grid, hipStream_t st) {
     }
 }
 
+// Launches with 128-row chunks hand out the chunks of the 16-bit experts first, then the others, each in expert
+// order: a 16-bit workgroup runs 110-130 us (bound by its weight stream) against 45-100 us for a 4-bit one, and the
+// launch ends when the last workgroup does, so the long ones must not start last.
+void launch_order(const DevExperts& ex, int E, int ct, uint8_t (&order)[MOE_MAX_EXPERTS]) {
+    int n = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int e = 0; e < E; ++e)
+            if (ct >= 8 ? (ex.e[e].prec == MOE_PREC_FP16) == (pass == 0) : pass == 0) order[n++] = (uint8_t)e;
+    for (; n < MOE_MAX_EXPERTS; ++n) order[n] = 0;
+}
+
 bool any_int8(const DevExperts& ex, int E) {
     for (int e = 0; e < E; ++e)
         if (ex.e[e].prec == MOE_PREC_INT8G64) return true;
@@ -1392,6 +1406,7 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
     a.in_offsets32 = (uint64_t)P * (uint64_t)d * 2u < (1ull << 32);
+    launch_order(ex, E, ct, a.order);
     const int up_rows = 32 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (f + up_rows - 1) / up_rows;
     dim3 grid(a.tiles, chunk_slots(rows, P, E, ct), 1);
@@ -1408,6 +1423,7 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
     a.in_offsets32 = (uint64_t)P * (uint64_t)f * 2u < (1ull << 32);
+    launch_order(ex, E, ct, a.order);
     const int down_rows = 64 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (d + down_rows - 1) / down_rows;
     dim3 grid(a.tiles * splits, chunk_slots(rows, P, E, ct), 1);
