@@ -116,6 +116,9 @@ STEPS4_ZIPF = Config("steps4_zipf", 1024, 2048, 8, 2, 420, (2, 3, 4, 5, 6, 7), z
 # The same with the 4-bit experts in front: experts 0 and 1 get 391 and 250 of the 840 rows, which run in chunks of 9
 # and 8 tiles (a 4-bit expert's chunks hold up to 192 rows, split evenly), expert 2 in one of 7.
 STEPS4_ZIPF_Q = Config("steps4_zipf_4bit_heavy", 1024, 2048, 8, 2, 420, (0, 1, 2, 4, 5), zipf=1.2)
+# One 16-bit expert (250 rows, one chunk of 16 tiles) between 4-bit ones: its chunk is handed out before those of
+# expert 0 (the launch order puts 16-bit experts first), so chunk index and expert order differ.
+STEPS4_ZIPF_MID = Config("steps4_zipf_16bit_second", 1024, 2048, 8, 2, 420, (0, 2, 3, 4, 5, 6, 7), zipf=1.2)
 # d and f multiples of 64 but not of 128: served by the shape-agnostic kernels.
 GENERIC = Config("generic", 192, 320, 4, 2, 9, (1, 2))
 # Smallest shape the batch-1 decode kernels take (d and f multiples of 2048), with a precision mix.

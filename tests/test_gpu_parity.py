@@ -9,8 +9,8 @@ torch = pytest.importorskip("torch")
 from paper_2407_14417_amd import binding as mm
 from paper_2407_14417_amd import synth
 from tests import common
-from tests.common import (TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q, build_workload,
-                          assert_ffn_close)
+from tests.common import (TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q, STEPS4_ZIPF_MID,
+                          build_workload, assert_ffn_close)
 from tests.gpu_common import dev, device_layer, device_mat
 
 pytestmark = pytest.mark.gpu
@@ -289,8 +289,8 @@ def _run_layer(layer, x_np, cfg):
     return out.cpu().numpy(), idx.cpu().numpy(), gate.cpu().numpy(), mm.moe_read_status(ws)
 
 
-@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q],
-                         ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TINY, MEDIUM, MEDIUM_ZIPF, ODD_STEPS, GENERIC, STEPS4, STEPS4_ZIPF, STEPS4_ZIPF_Q,
+                                 STEPS4_ZIPF_MID], ids=lambda c: c.name)
 def test_layer_forward(orc, cfg):
     wl = build_workload(cfg, orc)
     _say(f"layer_forward cfg={cfg.name}")
