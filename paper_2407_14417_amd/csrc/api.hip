@@ -59,7 +59,9 @@ constexpr int kDecodeUpBlocks = 1024;
 // Which kernels serve T tokens of a block: T == 1 the batch-1 kernels, otherwise the matrix-core path when
 // the shape allows it, else the shape-agnostic kernels.
 bool use_decode(const moe_layer* L, int T) { return T == 1 && decode_shape_ok(L->d_model, L->d_ff); }
-bool use_mfma(const moe_layer* L, int rows) { return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff); }
+bool use_mfma(const moe_layer* L, int rows) {
+    return rows > 1 && mfma_shape_ok(L->d_model, L->d_ff) && mfma_rows_ok(rows, L->d_model, L->d_ff);
+}
 
 MfmaPlan plan_for(const moe_layer* L, int rows) { return plan_mfma(rows, L->d_model, L->d_ff, L->n_experts); }
 

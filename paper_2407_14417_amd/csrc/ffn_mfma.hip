@@ -56,8 +56,6 @@ struct MfmaArgs {
     int tiles;                // tiles of weight rows (grid.x = tiles * splits)
     size_t split_stride;      // elements of y between two splits
     int unit_bytes;           // LDS bytes per A operand for weight staging: 4096 if any expert is 16-bit, else 2048
-    int in_offsets32;         // the input rows of this launch span less than 4 GB (the pipelined bodies address them
-                              // with 32-bit byte offsets)
     uint8_t order[MOE_MAX_EXPERTS];   // the experts in the order their chunks are handed out
     int32_t* status;
 };
@@ -214,14 +212,15 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     // ---- activation pieces this thread stages: column piece tid % PPR of rows tid / PPR + RPP i.
     // Rows past the end of the chunk repeat its last row: their products are computed and never stored.
     const int pcol = tid % PPR, pstep = pcol >> 4;     // pstep: which 128-column step of the stage the piece is in
-    const half_t* xrow[NP];
+    const gptr_t xbase = scalar_ptr(c.in + c.k_begin);
+    uint32_t xoff[NP];                                 // byte offsets: the input rows of a launch span less than 4 GB
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         int rr = tid / PPR + RPP * i;
         rr = rr < c.rows ? rr : c.rows - 1;
         const int g = c.begin + c.m0 + rr;
-        const size_t src = (UP && c.perm) ? (size_t)(c.perm[g] / c.top_k) : (size_t)g;
-        xrow[i] = c.in + src * K + c.k_begin + (pcol & 15) * 8;
+        const uint32_t src = (UP && c.perm) ? (uint32_t)(c.perm[g] / c.top_k) : (uint32_t)g;
+        xoff[i] = src * (uint32_t)K * 2 + (pcol & 15) * 16;
     }
     uint4_t xr[NP];
     auto load_x = [&](int stage) {
@@ -229,7 +228,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         step = step < last ? step : last;
         step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
 #pragma unroll
-        for (int i = 0; i < NP; ++i) xr[i] = *(const uint4_t*)(xrow[i] + step * kKTile);
+        for (int i = 0; i < NP; ++i)
+            xr[i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + step * (kKTile * 2) + fresh_offset(xoff[i]));
     };
     auto store_x = [&](int buf) {
         uint8_t* base = c.lds + buf * buf_bytes + (tid / PPR) * kStride + pcol * 16;
@@ -246,16 +246,17 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 
     // ---- scales and zeros of this lane's weight rows (4-bit): the wavefront owns NT/4 rows from n0 + wave * NT/4,
     // in tiles of 16; lane (r16, c4) looks after row r16 of each tile
-    const half_t* wscale[NA];
-    const half_t* wzero[NA];
+    gptr_t sbase[NA], zbase[NA];                       // uniform bases, one lane offset for both
+    uint32_t soff[NA];
 #pragma unroll
     for (int t = 0; t < NA; ++t) {
         const int tile = UP ? (t >> 1) : t;                        // up: operands (w1 tile0, w3 tile0, w1 tile1, w3 tile1)
         const DevMat& m = UP ? ((t & 1) ? ee.w3 : ee.w1) : ee.w2;
         int row = c.n0 + wave * (NT / 4) + tile * 16 + r16;
         row = row < N ? row : N - 1;                               // rows past the end repeat the last row, never stored
-        wscale[t] = QUANT ? m.scale + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
-        wzero[t] = QUANT ? m.zero + (size_t)row * (K >> 6) + (c.k_begin >> 6) : nullptr;
+        sbase[t] = QUANT ? scalar_ptr(m.scale + (c.k_begin >> 6)) : nullptr;
+        zbase[t] = QUANT ? scalar_ptr(m.zero + (c.k_begin >> 6)) : nullptr;
+        soff[t] = (uint32_t)row * (uint32_t)(K >> 6) * 2;
     }
 
     float4_t acc[NA][NCT];
@@ -287,8 +288,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
 #pragma unroll
         for (int t = 0; t < NA; ++t) {
-            dst[t][0] = *(const uint32_t*)(wscale[t] + step * 2);
-            dst[t][1] = *(const uint32_t*)(wzero[t] + step * 2);
+            dst[t][0] = *(const uint32_t MOEMIX_GLOBAL*)(sbase[t] + step * 4 + fresh_offset(soff[t]));
+            dst[t][1] = *(const uint32_t MOEMIX_GLOBAL*)(zbase[t] + step * 4 + fresh_offset(soff[t]));
         }
     };
     // Weights take a detour through LDS so that device memory is read in whole 128-byte lines: one load instruction
@@ -337,7 +338,8 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
                 for (int q = 0; q < UL; ++q)
                 {
-                    const uint4_t MOEMIX_GLOBAL* src = (const uint4_t MOEMIX_GLOBAL*)(cbase[t] + goff[t][hb] + byte0 + q * 128);
+                    const uint4_t MOEMIX_GLOBAL* src =
+                        (const uint4_t MOEMIX_GLOBAL*)(cbase[t] + (byte0 + q * 128) + fresh_offset(goff[t][hb]));
                     // launches with many activation rows per expert run several chunks of one expert side by side on
                     // the same XCD: the second reader of a weight line should find it in L2, so the line is not
                     // marked as used once there
@@ -1165,7 +1167,7 @@ __global__ __launch_bounds__(256) void grouped_mfma_kernel(const MfmaArgs a) {
     // chunks up to kDirectRows (direct_body), split evenly in whole tiles.
     const int n_steps = a.k_per_split / kKTile;
     // (launches with 128-row chunks have LDS for two 256-row stages)
-    const bool wide_ok = CT >= 8 && !(n_steps & 1) && a.in_offsets32;
+    const bool wide_ok = CT >= 8 && !(n_steps & 1);
     // (4-bit chunks of more than 128 rows save compute-unit time, not latency: one expert alone whose launch does not
     // fill the chip twice over is faster with more, smaller workgroups side by side -- 148 rows: 73 us in chunks of
     // 128 + 20 rows, 89 us in one chunk)
@@ -1377,6 +1379,11 @@ bool mfma_shape_ok(int d, int f) {
     return d % kKTile == 0 && f % kKTile == 0 && d >= 2 * kKTile && f >= 2 * kKTile && (uint64_t)d * (uint64_t)f * 2u < (1ull << 32);
 }
 
+// The kernels address the rows of their input (tokens, hidden rows) with 32-bit byte offsets from its start.
+bool mfma_rows_ok(int rows, int d, int f) {
+    return (uint64_t)rows * (uint64_t)(d > f ? d : f) * 2u < (1ull << 32);
+}
+
 MfmaPlan plan_mfma(int P, int d, int f, int E) {
     MfmaPlan p;
     const int avg = (P + E - 1) / E;              // rows per expert if the load were even
@@ -1405,7 +1412,6 @@ void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, 
     a.direct_expert = rows.direct_expert; a.direct_n = rows.direct_n;
     a.in = x; a.out = h; a.K = d; a.N = f; a.E = E; a.k_per_split = d; a.split_stride = 0; a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
-    a.in_offsets32 = (uint64_t)P * (uint64_t)d * 2u < (1ull << 32);
     launch_order(ex, E, ct, a.order);
     const int up_rows = 32 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (f + up_rows - 1) / up_rows;
@@ -1422,7 +1428,6 @@ void launch_ffn_down_mfma(const DevExperts& ex, int E, const RowMap& rows, int P
     a.in = h; a.out = y; a.K = f; a.N = d; a.E = E; a.k_per_split = f / splits; a.split_stride = split_stride;
     a.status = status;
     a.unit_bytes = staging_unit_bytes(ex, E, rows);
-    a.in_offsets32 = (uint64_t)P * (uint64_t)f * 2u < (1ull << 32);
     launch_order(ex, E, ct, a.order);
     const int down_rows = 64 * (ct <= 2 ? kNASmall : 4);
     a.tiles = (d + down_rows - 1) / down_rows;

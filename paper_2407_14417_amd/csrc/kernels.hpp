@@ -39,6 +39,7 @@ struct MfmaPlan {
     int down_splits;
 };
 bool mfma_shape_ok(int d, int f);
+bool mfma_rows_ok(int rows, int d, int f);
 MfmaPlan plan_mfma(int P, int d, int f, int E);
 void launch_ffn_up_mfma(const DevExperts& ex, int E, const RowMap& rows, int P, const half_t* x, int d, int f, half_t* h,
                         int ct, int32_t* status, hipStream_t st);
