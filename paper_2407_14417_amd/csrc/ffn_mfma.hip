@@ -258,6 +258,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         zbase[t] = QUANT ? scalar_ptr(m.zero + (c.k_begin >> 6)) : nullptr;
         soff[t] = (uint32_t)row * (uint32_t)(K >> 6) * 2;
     }
+    bool sz_aligned16 = true;                          // (what the 128-bit scale loads below ask of the arrays)
+#pragma unroll
+    for (int t = 0; t < NA; ++t)
+        sz_aligned16 = sz_aligned16 && !(((uintptr_t)sbase[t] | (uintptr_t)zbase[t]) & 15);
 
     float4_t acc[NA][NCT];
 #pragma unroll
@@ -290,6 +294,34 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
         for (int t = 0; t < NA; ++t) {
             dst[t][0] = *(const uint32_t MOEMIX_GLOBAL*)(sbase[t] + step * 4 + fresh_offset(soff[t]));
             dst[t][1] = *(const uint32_t MOEMIX_GLOBAL*)(zbase[t] + step * 4 + fresh_offset(soff[t]));
+        }
+    };
+    // 4-bit, at most 32 rows per chunk (the launch is bound by device memory), ranges of a multiple of 4 steps: scales
+    // and zeros of sixteen steps with one 128-bit load per lane and array (lane (r16, c4) fetches the eight groups of
+    // steps 16 S + 4 c4 .. + 3), so a row's 128-byte line of scales is asked for in two 64-byte requests instead of
+    // eight of 16 bytes; with the narrow requests the lines left L2 between requests and a launch fetched 29 % more
+    // than its algorithmic bytes.
+    constexpr bool kWideSz = INT4 && NA == kNASmall;
+    const bool wide_sz = kWideSz && !(n_steps & 3) && sz_aligned16;
+    uint4_t sq_cur[NA][2], sq_next[NA][2];
+    auto load_sq = [&](uint4_t (&dst)[NA][2], int S) {
+        int step = 16 * S + 4 * c4;
+        step = step < n_steps - 4 ? step : n_steps - 4;            // groups past the end repeat the last one (never used)
+        step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;   // (the rotation is a multiple of 4 steps)
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            dst[t][0] = *(const uint4_t MOEMIX_GLOBAL*)(sbase[t] + step * 4 + fresh_offset(soff[t]));
+            dst[t][1] = *(const uint4_t MOEMIX_GLOBAL*)(zbase[t] + step * 4 + fresh_offset(soff[t]));
+        }
+    };
+    auto load_sz_narrow = [&](uint4_t (&dst)[NA][2], int S) {      // the narrow form, kept in word 0 of the same registers
+        int step = 4 * S + c4;
+        step = step < last ? step : last;
+        step = step + c.rot < n_steps ? step + c.rot : step + c.rot - n_steps;
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            dst[t][0][0] = *(const uint32_t MOEMIX_GLOBAL*)(sbase[t] + step * 4 + fresh_offset(soff[t]));
+            dst[t][1][0] = *(const uint32_t MOEMIX_GLOBAL*)(zbase[t] + step * 4 + fresh_offset(soff[t]));
         }
     };
     // Weights take a detour through LDS so that device memory is read in whole 128-byte lines: one load instruction
@@ -371,7 +403,9 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
     };
 
     load_x(0);
-    if (QUANT) load_sz(sz_cur, 0);
+    if (kWideSz && wide_sz) load_sq(sq_cur, 0);
+    else if (kWideSz) load_sz_narrow(sq_cur, 0);
+    else if (QUANT) load_sz(sz_cur, 0);
     load_unit(0);
     stage_to_lds();
     load_unit(1);
@@ -391,20 +425,36 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     load_x(stage + 2);
                 }
                 if (INT4) {
-                    if (g % 4 == 0) {
+                    if (kWideSz && wide_sz) {
+                        if (g % 4 == 0 && (step & 15) == 0) {
+                            if (step > 0) {
+#pragma unroll
+                                for (int t = 0; t < NA; ++t) { sq_cur[t][0] = sq_next[t][0]; sq_cur[t][1] = sq_next[t][1]; }
+                            }
+                            load_sq(sq_next, step / 16 + 1);
+                        }
+                    } else if (g % 4 == 0) {
                         if (step > 0) {
 #pragma unroll
-                            for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+                            for (int t = 0; t < NA; ++t) {
+                                if (kWideSz) { sq_cur[t][0][0] = sq_next[t][0][0]; sq_cur[t][1][0] = sq_next[t][1][0]; }
+                                else { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
+                            }
                         }
-                        load_sz(sz_next, step / 4 + 1);
+                        if (kWideSz) load_sz_narrow(sq_next, step / 4 + 1);
+                        else load_sz(sz_next, step / 4 + 1);
                     }
                     if (g % 2 == 0) lds_to_operands(step >> 1);
                     half2_t s2[NA], z2[NA];
-                    const int src = (r16 + 16 * (g & 3)) * 4;       // the lane of this row that fetched this step's scales
+                    // the lane of this row that fetched this step's scales: the step's place among four, or (wide
+                    // requests) its group of four steps' place among four, where the step's word is g & 3
+                    const int src = (r16 + 16 * ((kWideSz && wide_sz) ? (step >> 2) & 3 : g & 3)) * 4;
 #pragma unroll
                     for (int t = 0; t < NA; ++t) {
-                        const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][0]);
-                        const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sz_cur[t][1]);
+                        const uint32_t sw = !kWideSz ? sz_cur[t][0] : wide_sz ? sq_cur[t][0][g & 3] : sq_cur[t][0][0];
+                        const uint32_t zw = !kWideSz ? sz_cur[t][1] : wide_sz ? sq_cur[t][1][g & 3] : sq_cur[t][1][0];
+                        const uint32_t sd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sw);
+                        const uint32_t zd = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)zw);
                         s2[t] = as_half2(__builtin_amdgcn_perm(sd, sd, sel));
                         z2[t] = as_half2(__builtin_amdgcn_perm(zd, zd, sel));
                     }
