@@ -66,7 +66,7 @@ typedef enum {
 /* The "quantized?" attribute of the paper's expert table (§3). */
 typedef enum { MOE_PREC_FP16 = 0, MOE_PREC_INT4G64 = 1, MOE_PREC_INT8G64 = 2 } moe_prec;
 
-/* One weight matrix [out, in] in device memory. */
+/* One weight matrix [out, in] in device memory, rows end to end; every pointer 16-byte aligned (MOE_EINVAL otherwise). */
 typedef struct {
     const void* data;  /* device: fp16 [out,in]; uint8 [out,in/2] of packed 4-bit codes; or uint8 [out,in] of 8-bit codes */
     const void* scale; /* device: fp16 [out,in/64]; NULL for a 16-bit matrix */

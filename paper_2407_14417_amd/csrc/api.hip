@@ -48,6 +48,12 @@ int check_layer(const moe_layer* L) {
         if (x.resident && x.prec != MOE_PREC_FP16 &&
             (!x.w1.scale || !x.w1.zero || !x.w3.scale || !x.w3.zero || !x.w2.scale || !x.w2.zero))
             return fail(MOE_EINVAL, "expert %d: quantized matrices need scale and zero", e);
+        if (x.resident) {   // the kernels read weights, scales and zeros with 128-bit loads
+            const moe_mat* mats[3] = {&x.w1, &x.w3, &x.w2};
+            for (const moe_mat* m : mats)
+                if (((uintptr_t)m->data | (uintptr_t)m->scale | (uintptr_t)m->zero) & 15)
+                    return fail(MOE_EINVAL, "expert %d: data, scale and zero must be 16-byte aligned", e);
+        }
     }
     return MOE_OK;
 }

@@ -57,6 +57,26 @@ def test_bad_layers_are_rejected_on_the_host(L, kwargs, code):
     assert L.moe_layer_forward(ctypes.byref(lay), 1, 1, 1, None, None, 256, 1 << 30, None) == code
 
 
+def test_misaligned_matrices_are_rejected_on_the_host(L):
+    """Weights, scales and zeros are read with 128-bit loads: a resident expert whose pointers are not 16-byte
+    aligned is refused before any launch."""
+    ex = (mm.CExpert * 4)()
+    for e in range(4):
+        ex[e].prec, ex[e].resident = mm.PREC_FP16, 1
+        for m in (ex[e].w1, ex[e].w3, ex[e].w2):
+            m.data = 4096
+    lay, _ = _layer(experts=ex)
+    assert L.moe_workspace_bytes(ctypes.byref(lay), 4) > 0
+    ex[2].w3.data = 4096 + 8
+    assert L.moe_route(ctypes.byref(lay), 1, 1, 1, 1, None) == mm.MOE_EINVAL
+    assert b"16-byte aligned" in L.moe_last_error()
+    ex[2].w3.data = 4096
+    ex[1].prec = mm.PREC_INT4G64
+    for m in (ex[1].w1, ex[1].w3, ex[1].w2):
+        m.scale, m.zero = 8192, 8192 + 2
+    assert L.moe_route(ctypes.byref(lay), 1, 1, 1, 1, None) == mm.MOE_EINVAL
+
+
 def test_null_and_size_arguments(L):
     lay, _ = _layer()
     assert L.moe_route(ctypes.byref(lay), None, 1, 1, 1, None) == mm.MOE_EINVAL
