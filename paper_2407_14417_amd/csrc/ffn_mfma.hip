@@ -354,8 +354,11 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
             goff[t][hb] = (uint32_t)row * (uint32_t)(INT4 ? (K >> 1) : INT8 ? K : 2 * K) + (lane & 7) * 16;
         }
     }
-    auto load_unit = [&](int unit) {           // a unit past the end repeats the last one (never used)
-        unit = unit < last_unit ? unit : last_unit;
+    auto load_unit = [&](int unit) {
+        // No loads for a unit past the end (the registers keep what they hold; it is never used).  Repeating the last
+        // unit instead looked free and was not: a streamed line has left L2 once it has been read, so every workgroup
+        // fetched its last line of every row three times (batched decode: + 11 % of the code bytes).
+        if (unit > last_unit) return;
         {   // (a rotated range has an even number of steps: whole units)
             const int urot = INT4 ? c.rot >> 1 : c.rot, units = INT4 ? n_steps >> 1 : n_steps;
             if (c.rot) unit = unit + urot < units ? unit + urot : unit + urot - units;
@@ -431,7 +434,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
                                 for (int t = 0; t < NA; ++t) { sq_cur[t][0] = sq_next[t][0]; sq_cur[t][1] = sq_next[t][1]; }
                             }
-                            load_sq(sq_next, step / 16 + 1);
+                            if (step + 16 < n_steps) load_sq(sq_next, step / 16 + 1);   // (nothing past the end: see load_unit)
                         }
                     } else if (g % 4 == 0) {
                         if (step > 0) {
@@ -441,8 +444,10 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                                 else { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
                             }
                         }
-                        if (kWideSz) load_sz_narrow(sq_next, step / 4 + 1);
-                        else load_sz(sz_next, step / 4 + 1);
+                        if (step + 4 < n_steps) {                   // (nothing past the end: see load_unit)
+                            if (kWideSz) load_sz_narrow(sq_next, step / 4 + 1);
+                            else load_sz(sz_next, step / 4 + 1);
+                        }
                     }
                     if (g % 2 == 0) lds_to_operands(step >> 1);
                     half2_t s2[NA], z2[NA];
@@ -480,7 +485,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
 #pragma unroll
                             for (int t = 0; t < NA; ++t) { sz_cur[t][0] = sz_next[t][0]; sz_cur[t][1] = sz_next[t][1]; }
                         }
-                        load_sz(sz_next, step / 4 + 1);
+                        if (step + 4 < n_steps) load_sz(sz_next, step / 4 + 1);
                     }
                     lds_to_operands(step);
                     half2_t s2[NA], z2[NA];
@@ -601,7 +606,9 @@ __device__ __forceinline__ void direct_body(const TileCtx& c, const DevExpert& e
         doff[t] = (uint32_t)row * (uint32_t)(2 * K) + c4 * 16;
     }
     uint4_t ar[R][NA];
-    auto load_a = [&](int slot, int sub) {                         // sub-steps past the end repeat the last one
+    // (sub-steps past the end repeat the last one: a branch around the loads costs more than the loads -- the
+    // compiler then waits as if they had not been issued, which drains the ring: prefill step + 5 %)
+    auto load_a = [&](int slot, int sub) {
         sub = sub < last_sub ? sub : last_sub;
         sub = sub + 4 * c.rot <= last_sub ? sub + 4 * c.rot : sub + 4 * c.rot - 4 * n_steps;
 #pragma unroll
