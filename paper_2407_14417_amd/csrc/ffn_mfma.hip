@@ -426,6 +426,11 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                 if (g % SPB == 0) {
                     store_x((stage + 1) & 1);                       // past the last stage this writes data nobody reads
                     load_x(stage + 2);
+                    // 4-bit, two steps per stage = one unit of codes per stage: the unit that takes the place of the
+                    // one used up in the last stage is asked for here, after the activation loads.  Loads return in
+                    // the order of their issue, so an activation load (a hit in L2) issued behind a load of weights
+                    // from device memory is held back as long as that one takes.
+                    if (INT4 && SPB == 2 && step > 0) load_unit(((step - 1) >> 1) + 2);
                 }
                 if (INT4) {
                     if (kWideSz && wide_sz) {
@@ -477,7 +482,7 @@ __device__ __forceinline__ void tile_body(const TileCtx& c, const DevExpert& ee,
                     }
                     if (g % 2 == 1 || step == last) {               // the pair is used up: the next one takes its place
                         stage_to_lds();
-                        load_unit((step >> 1) + 2);
+                        if (SPB != 2) load_unit((step >> 1) + 2);   // (two steps per stage: at the next stage's start)
                     }
                 } else if (INT8) {
                     if (g % 4 == 0) {
