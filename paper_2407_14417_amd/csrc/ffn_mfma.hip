@@ -770,13 +770,17 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
         const uint32_t src = (UP && c.perm) ? (uint32_t)(c.perm[g] / c.top_k) : (uint32_t)g;
         xoff[i] = src * (uint32_t)K * 2 + (tid & 15) * 16;
     }
-    uint4_t xr[NCT];
+    // Chunks of at most 6 tiles have the registers for two stages of activations under way (XD = 2: a piece is asked
+    // for two steps before it goes to LDS, in the register set of its stage's parity); their steps are short (1.6 us
+    // at 3 tiles), and a piece that has left L2 takes longer than that.
+    constexpr int XD = NCT <= 6 ? 2 : 1;
+    uint4_t xr[XD][NCT];
     uint8_t* const xst = c.lds + (tid >> 4) * kRowBytes + (((tid & 15) ^ (tid >> 4)) * 16);
     auto load_x1 = [&](int i, int stage) {
-        xr[i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + phys_step(stage) * kRowBytes + fresh_offset(xoff[i]));
+        xr[stage & (XD - 1)][i] = *(const uint4_t MOEMIX_GLOBAL*)(xbase + phys_step(stage) * kRowBytes + fresh_offset(xoff[i]));
     };
     auto store_x1 = [&](int i, int stage) {
-        const half8_t h = __builtin_bit_cast(half8_t, xr[i]);
+        const half8_t h = __builtin_bit_cast(half8_t, xr[stage & (XD - 1)][i]);
         *(half8_t*)(xst + (stage & 1) * kStageBytes + i * (16 * kRowBytes)) =
             half8_t{h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
     };
@@ -864,6 +868,10 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
     load_sz(sz_a, 0);
 #pragma unroll
     for (int i = 0; i < NCT; ++i) { store_x1(i, 0); load_x1(i, 1); }
+    if (XD == 2) {
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) load_x1(i, 2);
+    }
     pin_schedule();
 #pragma unroll
     for (int u = 0; u < R; ++u) load_a(u, u);
@@ -903,7 +911,7 @@ __device__ __forceinline__ void quant4_body(const TileCtx& c, const DevExpert& e
                 for (int j = 0; j < NCT; ++j) {
                     if (sb < 3 && j < PPS && sb * PPS + j < NCT) {   // stage step + 1 to LDS, stage step + 2 on its way
                         store_x1(sb * PPS + j, step + 1);
-                        load_x1(sb * PPS + j, step + 2);
+                        load_x1(sb * PPS + j, step + 1 + XD);
                     }
                     bq[(u + 1) & 1][j] = *(const half8_t*)((sb < 3 ? cur : nxt) + b_off[nword] + j * (16 * kRowBytes));
                     // The sub-step's 4 NCT products and, spread evenly between them, the 52 instructions that expand
